@@ -1,0 +1,192 @@
+"""ctypes front end of the CPU oracle (bcq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Tests, the smoke check and the benchmark's
+cpu_baseline leg import this module; the GPU package never does, and this module
+imports nothing from it.  All arithmetic lives in bcq_oracle.c (fp64, naive
+loops, AlphaTuning Section 3 Eq. 1-2, Section 4.1 Eq. 3-4, Appendix C Eq. ap1-ap3);
+this file only marshals numpy arrays and builds the shared object with gcc when
+it is missing or older than its source.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bcq_oracle.c")
+_LIB = os.path.join(_HERE, "libbcq_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile bcq_oracle.c -> libbcq_oracle.so (plain -O2: no fast-math, no reassociation)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".%d.tmp" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.orc_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+_I64 = ctypes.c_int64
+_INT = ctypes.c_int
+_DBL = ctypes.c_double
+
+
+def num_threads():
+    return int(_load().orc_num_threads())
+
+
+def quantize(W, q, with_margin=False):
+    """Greedy BCQ (Appendix C).  W[N,K] fp32 -> alpha[q,N] fp32, planes[q,N,K] int8 (+-1)."""
+    W = _f32(W)
+    N, K = W.shape
+    alpha = np.empty((q, N), np.float32)
+    planes = np.empty((q, N, K), np.int8)
+    margin = np.empty((q, N), np.float64) if with_margin else None
+    _load().orc_quantize(_p(W), _I64(N), _I64(K), _INT(q), _p(alpha), _p(planes),
+                         _p(margin) if with_margin else None)
+    return (alpha, planes, margin) if with_margin else (alpha, planes)
+
+
+def quantize_row_forced(w, q, alpha_in, force):
+    """Greedy BCQ of one row with alpha_i replaced by alpha_in[i] where force[i]."""
+    w = _f32(w)
+    K = w.shape[0]
+    alpha_in = _f32(alpha_in)
+    force = np.ascontiguousarray(force, dtype=np.uint8)
+    alpha = np.empty((q,), np.float32)
+    planes = np.empty((q, K), np.int8)
+    _load().orc_quantize_row_forced(_p(w), _I64(K), _INT(q), _p(alpha_in), _p(force), _p(alpha), _p(planes))
+    return alpha, planes
+
+
+def pack(planes):
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    assert K % 32 == 0
+    packed = np.empty((q, N, K // 32), np.uint32)
+    _load().orc_pack(_p(planes), _I64(N), _I64(K), _INT(q), _p(packed))
+    return packed
+
+
+def unpack(packed, K):
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    q, N, Kw = packed.shape
+    assert Kw * 32 == K
+    planes = np.empty((q, N, K), np.int8)
+    _load().orc_unpack(_p(packed), _I64(N), _I64(K), _INT(q), _p(planes))
+    return planes
+
+
+def dequant(alpha, planes):
+    """Eq. 1: What = sum_i diag(alpha_i) B_i in fp64."""
+    alpha = _f32(alpha)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    What = np.empty((N, K), np.float64)
+    _load().orc_dequant(_p(alpha), _p(planes), _I64(N), _I64(K), _INT(q), _p(What))
+    return What
+
+
+def fwd(alpha, planes, x):
+    """Eq. 2: y[T,N] fp64.  x[T,K] holds the exact input values as fp32."""
+    alpha, x = _f32(alpha), _f32(x)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = x.shape[0]
+    assert x.shape == (T, K) and alpha.shape == (q, N)
+    y = np.empty((T, N), np.float64)
+    _load().orc_fwd(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _INT(q), _p(y))
+    return y
+
+
+def fwd_at(alpha, planes, x, tt, nn):
+    alpha, x = _f32(alpha), _f32(x)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = x.shape[0]
+    tt, nn = _i64(tt), _i64(nn)
+    out = np.empty((tt.shape[0],), np.float64)
+    _load().orc_fwd_at(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _INT(q),
+                       _p(tt), _p(nn), _I64(tt.shape[0]), _p(out))
+    return out
+
+
+def bwd_input(alpha, planes, dy):
+    """Eq. 3: dx[T,K] fp64."""
+    alpha, dy = _f32(alpha), _f32(dy)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = dy.shape[0]
+    assert dy.shape == (T, N)
+    dx = np.empty((T, K), np.float64)
+    _load().orc_bwd_input(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _p(dx))
+    return dx
+
+
+def bwd_input_at(alpha, planes, dy, tt, kk):
+    alpha, dy = _f32(alpha), _f32(dy)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = dy.shape[0]
+    tt, kk = _i64(tt), _i64(kk)
+    out = np.empty((tt.shape[0],), np.float64)
+    _load().orc_bwd_input_at(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q),
+                             _p(tt), _p(kk), _I64(tt.shape[0]), _p(out))
+    return out
+
+
+def bwd_alpha(planes, x, dy, q_train=None, grad_scale=1.0):
+    """Eq. 4 read as the gradient of Eq. 2: dalpha[q_train,N] fp64."""
+    x, dy = _f32(x), _f32(dy)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = x.shape[0]
+    q_train = q if q_train is None else q_train
+    assert x.shape == (T, K) and dy.shape == (T, N) and 1 <= q_train <= q
+    out = np.empty((q_train, N), np.float64)
+    _load().orc_bwd_alpha(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _INT(q_train),
+                          _DBL(grad_scale), _p(out))
+    return out
+
+
+def bwd_alpha_rows(planes, x, dy, rows, q_train=None, grad_scale=1.0):
+    x, dy = _f32(x), _f32(dy)
+    planes = np.ascontiguousarray(planes, dtype=np.int8)
+    q, N, K = planes.shape
+    T = x.shape[0]
+    q_train = q if q_train is None else q_train
+    rows = _i64(rows)
+    out = np.empty((q_train, rows.shape[0]), np.float64)
+    _load().orc_bwd_alpha_rows(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _INT(q_train),
+                               _DBL(grad_scale), _p(rows), _I64(rows.shape[0]), _p(out))
+    return out
+
+
+def storage_bytes(N, K, q, g=None):
+    """Bytes of a BCQ matrix with 1-bit signs and fp32 scales: q*(N*K/8 + 4*N*K/g) (Table 1)."""
+    g = K if g is None else g
+    return q * (N * K // 8 + 4 * N * K // g)

@@ -1,0 +1,336 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test names the passage of AlphaTuning (arXiv 2210.03858) it pins.  The checks are
+closed forms, invariants, equivariances, brute force on tiny rows, reductions to a numpy
+library routine and exact integer cases, chosen so that a dropped term, a wrong sign or
+index, or a transposed operand in the oracle fails at least one of them.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2210_03858_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _residuals(W, alpha, planes):
+    """r_i = w - sum_{j<=i} alpha_j b_j in fp64, rebuilt from the oracle's outputs with numpy."""
+    r = W.astype(np.float64)
+    out = [r.copy()]
+    for i in range(alpha.shape[0]):
+        r = r - alpha[i].astype(np.float64)[:, None] * planes[i].astype(np.float64)
+        out.append(r.copy())
+    return out
+
+
+# ---------------------------------------------------------------- quantizer (Appendix C)
+
+def test_q1_closed_form(oracle):
+    """Eq. ap1: b* = sign(w), alpha* = w^T b* / n = mean |w|, with a correctly rounded sum."""
+    W = synth.weights(1, "out", 64, 1024)
+    alpha, planes, margin = oracle.quantize(W, 1, with_margin=True)
+    assert np.array_equal(planes[0], np.where(W >= 0, 1, -1).astype(np.int8))
+    for n in range(W.shape[0]):
+        exact = math.fsum(abs(float(v)) for v in W[n]) / W.shape[1]
+        if margin[0, n] > 1e-12:
+            assert alpha[0, n] == np.float32(exact)
+        else:  # the fp64 sum lies on a rounding boundary of fp32: either neighbour is right
+            assert abs(float(alpha[0, n]) - exact) <= np.spacing(np.float32(exact))
+
+
+def test_sign_of_zero_and_zero_row(oracle):
+    """sign(0) = +1 (also for -0.0); an all-zero row gives alpha = 0 and all signs +1."""
+    W = np.zeros((2, 32), np.float32)
+    W[1, :4] = [0.0, -0.0, 1.0, -1.0]
+    alpha, planes = oracle.quantize(W, 2)
+    assert np.all(alpha[:, 0] == 0) and np.all(planes[:, 0] == 1)
+    assert list(planes[0, 1, :4]) == [1, 1, 1, -1]
+    assert alpha[0, 1] == np.float32(2.0 / 32)
+
+
+@pytest.mark.parametrize("q", [2, 3, 4])
+def test_greedy_recurrence_invariants(oracle, q):
+    """Eq. ap2-ap3: b_i = sign(r_{i-1}); alpha_i = mean|r_{i-1}|; hence r_i is orthogonal to b_i and
+    ||r_i||^2 = ||r_{i-1}||^2 - K alpha_i^2 (up to the fp32 rounding of alpha); Fig. 2: error falls with q."""
+    W = synth.weights(2, "qkv", 48, 1024)
+    K = W.shape[1]
+    alpha, planes = oracle.quantize(W, q)
+    res = _residuals(W, alpha, planes)
+    for i in range(q):
+        prev, cur = res[i], res[i + 1]
+        assert np.array_equal(planes[i], np.where(prev >= 0, 1, -1).astype(np.int8))
+        mean_abs = np.abs(prev).mean(axis=1)
+        assert np.allclose(alpha[i], mean_abs, rtol=1e-7, atol=0)
+        dots = (cur * planes[i]).sum(axis=1)  # r_i . b_i = 0 for the unrounded alpha
+        assert np.all(np.abs(dots) <= K * mean_abs * 1.2e-7 + 1e-300)
+        n_prev, n_cur = (prev ** 2).sum(axis=1), (cur ** 2).sum(axis=1)
+        assert np.allclose(n_prev - n_cur, K * alpha[i].astype(np.float64) ** 2, rtol=1e-6)
+        assert np.all(n_cur <= n_prev)
+
+
+def test_equivariances(oracle):
+    """Exact symmetries of Eq. ap1-ap3: negation flips signs only; scaling by a power of two scales alpha
+    only; permuting the columns permutes the signs and leaves alpha (up to the order of one fp64 sum)."""
+    W = synth.weights(3, "out", 40, 1280)
+    assert not np.any(W == 0)
+    q = 3
+    a0, b0, m0 = oracle.quantize(W, q, with_margin=True)
+    a1, b1 = oracle.quantize(-W, q)
+    assert np.array_equal(a0, a1) and np.array_equal(b0, -b1)
+    a2, b2 = oracle.quantize(W * np.float32(8.0), q)
+    assert np.array_equal(a2, a0 * np.float32(8.0)) and np.array_equal(b2, b0)
+    perm = _rng(5).permutation(W.shape[1])
+    a3, b3, m3 = oracle.quantize(W[:, perm], q, with_margin=True)
+    safe = np.logical_and(m0 > 1e-10, m3 > 1e-10).all(axis=0)
+    assert safe.sum() >= W.shape[0] - 1
+    assert np.array_equal(a3[:, safe], a0[:, safe])
+    assert np.array_equal(b3[:, safe], b0[:, safe][:, :, perm])
+
+
+def _best_error(w, q):
+    """Brute force over all sign choices; for each, the least-squares alpha of Eq. ap4."""
+    K = w.shape[0]
+    best = np.inf
+    all_b = np.array(list(itertools.product((-1.0, 1.0), repeat=K)))
+    for combo in itertools.combinations_with_replacement(range(all_b.shape[0]), q):
+        B = all_b[list(combo)].T  # K x q
+        coef, *_ = np.linalg.lstsq(B, w, rcond=None)
+        best = min(best, float(((w - B @ coef) ** 2).sum()))
+    return best
+
+
+def test_brute_force_tiny_rows(oracle):
+    """q = 1: Eq. ap1 is the analytic optimum, so greedy equals brute force.  q = 2: greedy is a heuristic,
+    so the brute-force optimum is no worse, and the greedy error is no worse than its own q = 1 error."""
+    rng = _rng(11)
+    for trial in range(6):
+        K = 6
+        w = rng.standard_normal(K).astype(np.float32)
+        errs = {}
+        for q in (1, 2):
+            alpha, planes = oracle.quantize(w[None, :], q)
+            rec = (alpha[:, 0, None].astype(np.float64) * planes[:, 0, :]).sum(axis=0)
+            errs[q] = float(((w - rec) ** 2).sum())
+        assert errs[1] == pytest.approx(_best_error(w.astype(np.float64), 1), rel=1e-6)
+        best2 = _best_error(w.astype(np.float64), 2)
+        assert best2 <= errs[2] * (1 + 1e-9)
+        assert errs[2] <= errs[1]
+
+
+def test_gaussian_statistics(oracle):
+    """Closed form for i = 1 on Gaussian weights: alpha_1 / sigma -> sqrt(2/pi), relative MSE -> 1 - 2/pi."""
+    sigma = 0.02
+    W = synth.weights(4, "mlp_up", 256, 4096, std=sigma)
+    alpha, planes = oracle.quantize(W, 4)
+    assert float(alpha[0].mean()) / sigma == pytest.approx(math.sqrt(2 / math.pi), rel=2e-3)
+    res = _residuals(W, alpha, planes)
+    rel = [float((r ** 2).sum() / (res[0] ** 2).sum()) for r in res]
+    assert rel[1] == pytest.approx(1 - 2 / math.pi, rel=5e-3)
+    assert all(rel[i + 1] < rel[i] for i in range(4))
+    assert np.all(alpha[1:] < alpha[:-1])  # each residual is smaller than the one before
+
+
+def test_forced_alpha_rerun(oracle):
+    """Re-running a row with its own alphas forced reproduces it; forcing a neighbour fp32 changes alpha only there."""
+    W = synth.weights(1, "out", 4, 1024)
+    alpha, planes = oracle.quantize(W, 3)
+    a, b = oracle.quantize_row_forced(W[2], 3, alpha[:, 2], [1, 1, 1])
+    assert np.array_equal(a, alpha[:, 2]) and np.array_equal(b, planes[:, 2])
+    forced = alpha[:, 2].copy()
+    forced[0] = np.nextafter(forced[0], np.float32(1.0))
+    a, b = oracle.quantize_row_forced(W[2], 3, forced, [1, 0, 0])
+    assert a[0] == forced[0] and np.array_equal(b[0], planes[0, 2])
+
+
+# ---------------------------------------------------------------- pack / unpack, storage (Table 1)
+
+def test_pack_hand_words(oracle):
+    """Bit j of word w is the sign of column 32w + j, 1 <=> +1."""
+    planes = -np.ones((1, 5, 64), np.int8)
+    planes[0, 0, :] = 1
+    planes[0, 2, 0] = 1
+    planes[0, 3, 31] = 1
+    planes[0, 4, 32 + 5] = 1
+    packed = oracle.pack(planes)
+    assert packed.shape == (1, 5, 2)
+    assert list(packed[0, 0]) == [0xFFFFFFFF, 0xFFFFFFFF]
+    assert list(packed[0, 1]) == [0, 0]
+    assert list(packed[0, 2]) == [1, 0]
+    assert list(packed[0, 3]) == [0x80000000, 0]
+    assert list(packed[0, 4]) == [0, 1 << 5]
+
+
+def test_pack_roundtrip(oracle):
+    rng = _rng(3)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(3, 17, 96))
+    packed = oracle.pack(planes)
+    assert np.array_equal(oracle.unpack(packed, 96), planes)
+    words = rng.integers(0, 2 ** 32, size=(2, 9, 4), dtype=np.uint64).astype(np.uint32)
+    assert np.array_equal(oracle.pack(oracle.unpack(words, 128)), words)
+    # independent definition with numpy's bit packer
+    ref = np.packbits((planes > 0).astype(np.uint8), axis=-1, bitorder="little").view(np.uint32)
+    assert np.array_equal(ref.reshape(packed.shape), packed)
+
+
+def test_table1_storage_sizes(oracle):
+    """Table 1: quantized sizes for h = 1024; packed planes + fp32 scales reproduce the printed MB."""
+    h = 1024
+    checked = 0
+    for line in open(os.path.join(GOLDEN, "table1_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, nm, km, gm, m1, m2, m3, usable = line.split()
+        if usable != "1":
+            continue
+        N, K, g = int(nm) * h, int(km) * h, int(float(gm) * h)
+        for q, printed in zip((1, 2, 3), (m1, m2, m3)):
+            mb = oracle.storage_bytes(N, K, q, g) / 1e6
+            assert abs(mb - float(printed)) <= 0.0051
+            checked += 1
+        if g == K:  # what pack really emits for the row-wise case
+            planes = np.ones((1, N, K), np.int8)
+            assert oracle.pack(planes).nbytes + 4 * N == oracle.storage_bytes(N, K, 1)
+    assert checked == 15
+
+
+def test_table2_trainable_parameter_counts():
+    """Table 2 / Table 7: training alpha_1 only trains one fp32 per scale group; with alpha[q][N] that is
+    the number of rows (groups) of all quantized layers."""
+    for line in open(os.path.join(GOLDEN, "table2_trainable.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, h, layers, per_block, printed = line.split()
+        h, layers, per_block = int(h), int(layers), int(per_block)
+        if per_block == 9:
+            rows = sum(synth.layer_shape(h, kind)[0] for kind in synth.LAYER_KINDS)
+            assert rows == 9 * h
+        count = per_block * h * layers
+        assert abs(count / 1e6 - float(printed)) < 0.006
+
+
+# ---------------------------------------------------------------- forward (Eq. 1, Eq. 2)
+
+def _case(seed, T, N, K, q):
+    rng = _rng(seed)
+    W = (0.02 * rng.standard_normal((N, K))).astype(np.float32)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    dy = rng.standard_normal((T, N)).astype(np.float32)
+    return W, x, dy
+
+
+def _what_numpy(alpha, planes):
+    return np.einsum("in,ink->nk", alpha.astype(np.float64), planes.astype(np.float64))
+
+
+def test_fwd_reduces_to_matmul(oracle):
+    """Eq. 2 equals the dense product X What^T with What of Eq. 1."""
+    T, N, K, q = 7, 24, 96, 3
+    W, x, _ = _case(21, T, N, K, q)
+    alpha, planes = oracle.quantize(W, q)
+    What = _what_numpy(alpha, planes)
+    assert np.allclose(oracle.dequant(alpha, planes), What, rtol=1e-15, atol=0)
+    y = oracle.fwd(alpha, planes, x)
+    assert y.shape == (T, N)
+    ref = x.astype(np.float64) @ What.T
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-14)
+    tt, nn = np.array([0, 3, 6, 6]), np.array([23, 0, 5, 23])
+    assert np.array_equal(oracle.fwd_at(alpha, planes, x, tt, nn), y[tt, nn])
+
+
+def test_fwd_exact_integer_case(oracle):
+    """Small-integer activations and power-of-two scales make every partial sum exact."""
+    rng = _rng(22)
+    T, N, K, q = 5, 12, 64, 3
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    e = rng.integers(-3, 3, size=(q, N))
+    alpha = np.ldexp(1.0, e).astype(np.float32)
+    x = rng.integers(-8, 9, size=(T, K)).astype(np.float32)
+    y = oracle.fwd(alpha, planes, x)
+    scaled = (np.ldexp(1.0, e + 3).astype(np.int64)[:, :, None] * planes.astype(np.int64)).sum(axis=0)  # 8 * What
+    ref = (x.astype(np.int64) @ scaled.T) / 8.0
+    assert np.array_equal(y, ref)
+
+
+def test_fwd_single_plane_unit_scale(oracle):
+    """q = 1, alpha = 1: y = X B^T."""
+    rng = _rng(23)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(1, 10, 32))
+    x = rng.standard_normal((4, 32)).astype(np.float32)
+    y = oracle.fwd(np.ones((1, 10), np.float32), planes, x)
+    assert np.allclose(y, x.astype(np.float64) @ planes[0].astype(np.float64).T, rtol=1e-13, atol=1e-14)
+
+
+# ---------------------------------------------------------------- backward (Eq. 3, Eq. 4)
+
+def test_bwd_input_adjoint_and_matmul(oracle):
+    """Eq. 3 is the adjoint of Eq. 2 in x: <dy, fwd(x)> = <bwd_input(dy), x>; and dX = dY What."""
+    T, N, K, q = 6, 40, 64, 2
+    W, x, dy = _case(31, T, N, K, q)
+    alpha, planes = oracle.quantize(W, q)
+    y = oracle.fwd(alpha, planes, x)
+    dx = oracle.bwd_input(alpha, planes, dy)
+    assert dx.shape == (T, K)
+    lhs, rhs = float((dy * y).sum()), float((dx * x).sum())
+    assert lhs == pytest.approx(rhs, rel=1e-11)
+    assert np.allclose(dx, dy.astype(np.float64) @ _what_numpy(alpha, planes), rtol=1e-12, atol=1e-14)
+    tt, kk = np.array([0, 5, 2]), np.array([63, 0, 17])
+    assert np.array_equal(oracle.bwd_input_at(alpha, planes, dy, tt, kk), dx[tt, kk])
+
+
+def test_bwd_input_finite_difference(oracle):
+    """Central differences of L = <dy, fwd(x)> in single entries of x (exact for a linear map up to rounding)."""
+    T, N, K, q = 3, 16, 32, 3
+    W, x, dy = _case(32, T, N, K, q)
+    alpha, planes = oracle.quantize(W, q)
+    dx = oracle.bwd_input(alpha, planes, dy)
+    for (t, k) in [(0, 0), (1, 17), (2, 31)]:
+        h = np.float32(0.25)
+        xp, xm = x.copy(), x.copy()
+        xp[t, k] += h
+        xm[t, k] -= h
+        step = float(xp[t, k]) - float(xm[t, k])
+        fd = float((dy * (oracle.fwd(alpha, planes, xp) - oracle.fwd(alpha, planes, xm))).sum()) / step
+        assert fd == pytest.approx(dx[t, k], rel=1e-9, abs=1e-12)
+
+
+def test_bwd_alpha_euler_crossform_fd(oracle):
+    """Eq. 4 as the gradient of Eq. 2: Euler identity <dy, fwd> = sum_i <alpha_i, dalpha_i> (fwd is linear in
+    alpha); the equal form dalpha_i[n] = sum_k B_i[n,k] (dY^T X)[n,k]; finite differences in single alphas."""
+    T, N, K, q = 9, 20, 64, 3
+    W, x, dy = _case(41, T, N, K, q)
+    alpha, planes = oracle.quantize(W, q)
+    da = oracle.bwd_alpha(planes, x, dy)
+    assert da.shape == (q, N)
+    y = oracle.fwd(alpha, planes, x)
+    assert float((dy * y).sum()) == pytest.approx(float((alpha.astype(np.float64) * da).sum()), rel=1e-11)
+    G = dy.astype(np.float64).T @ x.astype(np.float64)
+    assert np.allclose(da, (planes.astype(np.float64) * G[None]).sum(axis=2), rtol=1e-11, atol=1e-13)
+    for (i, n) in [(0, 0), (1, 7), (2, 19)]:
+        ap, am = alpha.copy(), alpha.copy()
+        h = np.float32(2.0 ** -6)
+        ap[i, n] += h
+        am[i, n] -= h
+        step = float(ap[i, n]) - float(am[i, n])
+        fd = float((dy * (oracle.fwd(ap, planes, x) - oracle.fwd(am, planes, x))).sum()) / step
+        assert fd == pytest.approx(da[i, n], rel=1e-9, abs=1e-12)
+
+
+def test_bwd_alpha_scale_and_subset(oracle):
+    """The 1/g_L factor of Eq. 4 is a plain multiplier; training alpha_1 only returns the first plane's rows."""
+    T, N, K, q = 5, 12, 96, 4
+    W, x, dy = _case(42, T, N, K, q)
+    _, planes = oracle.quantize(W, q)
+    full = oracle.bwd_alpha(planes, x, dy)
+    assert np.allclose(oracle.bwd_alpha(planes, x, dy, grad_scale=1.0 / K), full / K, rtol=1e-15)
+    first = oracle.bwd_alpha(planes, x, dy, q_train=1)
+    assert first.shape == (1, N) and np.array_equal(first[0], full[0])
+    rows = np.array([11, 0, 5])
+    assert np.array_equal(oracle.bwd_alpha_rows(planes, x, dy, rows), full[:, rows])
