@@ -1,0 +1,131 @@
+/*
+ * bcq.h - C ABI of the MI355X (gfx950) library for the binary-coding-quantized (BCQ) linear layer
+ * of AlphaTuning (arXiv 2210.03858).
+ *
+ * Model (Section 3 "BCQ Format", Eq. 1, row-wise quantization g = h_in):
+ *     W[N][K] ~= sum_{i=0..q-1} diag(alpha_i) * B_i ,   B_i in {-1,+1}^{N x K},  alpha_i in R^N.
+ * N = h_out (rows of W), K = h_in (columns of W, contraction length of the forward), T = n_b tokens.
+ * Plane index i is 0-based here (alpha_1 of the paper is alpha[0]).  Shapes follow Table 1:
+ * alpha[q][N] (always fp32, Section 4.2), sign planes [q][N][K].
+ *
+ * Canonical packed layout: packed[i][n][w], w < K/32, one uint32 per 32 consecutive columns;
+ * bit j (LSB = 0) of word w is the sign of B_i[n][32w + j]; 1 <=> +1, 0 <=> -1.
+ * Transposed twin (optional accelerator for the input gradient): packed_t[i][k][v], v < N/32;
+ * bit j of word v is the sign of B_i[32v + j][k].  It holds the same information as `packed`.
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or keeps them.  Arrays are dense row-major with the innermost extent as stride.
+ *   - Every data pointer must be 16-byte aligned (BCQ_ERR_ALIGN otherwise).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Arguments are
+ *     validated synchronously on the host; the work is enqueued on `stream` and the call returns
+ *     without waiting.  Outputs are valid once the stream has reached that point.
+ *   - `workspace` is optional device scratch owned by the caller, at least 16-byte aligned; its
+ *     contents before the call are ignored and after the call are unspecified (except where an
+ *     entry point documents a status word).  Pass NULL / 0 to make the library choose a path that
+ *     needs none (always available, possibly slower).  bcq_workspace_bytes() gives the size that
+ *     enables the fastest path; a non-NULL workspace smaller than that is BCQ_ERR_WORKSPACE.
+ *   - Return value: BCQ_OK or the first problem found; nothing is enqueued unless BCQ_OK.
+ *     Order of checks: NULL pointers, shapes, dtype, alignment, workspace, device.
+ *   - Limits: 1 <= q <= 8; K % 32 == 0; N, K, T >= 1; N*K and T*max(N,K) below 2^40.
+ *   - No global state besides per-device capability caches; calls on different streams may overlap
+ *     as long as their outputs and workspaces do not alias.
+ */
+#ifndef BCQ_H
+#define BCQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BCQ_OK = 0,
+    BCQ_ERR_NULL = 1,      /* a required pointer is NULL                                        */
+    BCQ_ERR_SHAPE = 2,     /* N,K,T < 1; q outside [1,8]; K % 32 != 0; q_train outside [1,q];
+                              N % 32 != 0 with a transposed twin; K above the quantizer's limit */
+    BCQ_ERR_DTYPE = 3,     /* dtype is neither BCQ_F32 nor BCQ_BF16, or op code unknown         */
+    BCQ_ERR_ALIGN = 4,     /* a data pointer or the workspace is not 16-byte aligned            */
+    BCQ_ERR_WORKSPACE = 5, /* workspace non-NULL but smaller than bcq_workspace_bytes()         */
+    BCQ_ERR_NONFINITE = 6, /* reserved: reported through bcq_quantize's status word, not returned */
+    BCQ_ERR_DEVICE = 7     /* no usable gfx950 device, or a HIP call failed                     */
+} bcq_status;
+
+typedef enum { BCQ_F32 = 0, BCQ_BF16 = 1 } bcq_dtype; /* element type of x, y, dy, dx */
+
+typedef enum {
+    BCQ_OP_QUANTIZE = 0,
+    BCQ_OP_FWD = 1,
+    BCQ_OP_BWD_INPUT = 2,
+    BCQ_OP_BWD_ALPHA = 3
+} bcq_op;
+
+/* Largest K bcq_quantize accepts (a whole row is kept in registers across the q planes). */
+#define BCQ_QUANTIZE_MAX_K 16384
+
+/* Static, NUL-terminated description of a status code. */
+const char* bcq_status_string(bcq_status s);
+
+/* ABI version, bumped on any signature change. */
+int bcq_abi_version(void);
+
+/* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
+ * T is ignored for BCQ_OP_QUANTIZE.  Host-only: touches no device. */
+bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, int dtype, size_t* out);
+
+/* Greedy BCQ quantizer (Appendix C: Eq. ap1 for the first plane, Eq. ap2-ap3 for the others).
+ * Per row n: r = W[n][:] in fp64; for i = 0..q-1: B_i = (r >= 0 ? +1 : -1) (so sign(0) = +1),
+ * alpha_i = fp32( sum_k |r_k| / K ) with the sum in fp64, r -= alpha_i * B_i using the ROUNDED alpha_i.
+ *   W          [N][K] fp32, in
+ *   alpha      [q][N] fp32, out
+ *   packed     [q][N][K/32] uint32 canonical layout, out
+ *   planes_i8  [q][N][K] int8 holding -1/+1, out; may be NULL
+ *   workspace  optional; if non-NULL (>= 16 bytes) its first int32 is a status word, set to the number of
+ *              rows of W that hold a NaN or Inf (0 = all finite); outputs of such rows are unspecified.
+ * K <= BCQ_QUANTIZE_MAX_K, else BCQ_ERR_SHAPE. */
+bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
+                        int8_t* planes_i8, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bit-plane pack (Table 1 gives the index order B:(q, h_out, h_in); footnote of Section 3: contiguous rows).
+ *   planes_i8 [q][N][K] int8, in.  Only the sign of each byte is read: v >= 0 -> bit 1 (+1), v < 0 -> bit 0.
+ *   packed    [q][N][K/32] uint32 canonical layout, out. */
+bcq_status bcq_pack(const int8_t* planes_i8, int64_t N, int64_t K, int q, uint32_t* packed, void* stream);
+
+/* Inverse of bcq_pack: writes exactly -1 or +1 into planes_i8[q][N][K]. */
+bcq_status bcq_unpack(const uint32_t* packed, int64_t N, int64_t K, int q, int8_t* planes_i8, void* stream);
+
+/* Builds the transposed twin packed_t[q][K][N/32] from the canonical packed[q][N][K/32] (same signs,
+ * bits running along N).  Needs N % 32 == 0.  One-time, like bcq_pack; used by bcq_linear_bwd_input. */
+bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* packed_t,
+                               void* stream);
+
+/* Forward (Eq. 2): y[t][n] = sum_i alpha_i[n] * sum_k B_i[n][k] * x[t][k], fp32 accumulation,
+ * result rounded to `dtype` (bf16: round to nearest even).  W is never materialised in memory.
+ *   packed [q][N][K/32] in; alpha [q][N] fp32 in; x [T][K] `dtype` in; y [T][N] `dtype` out. */
+bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                          int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* Input gradient (Eq. 3): dx[t][k] = sum_n dy[t][n] * sum_i alpha_i[n] * B_i[n][k].
+ *   packed [q][N][K/32] in; packed_t [q][K][N/32] in, may be NULL (then a slower path that reads only
+ *   `packed` is used; non-NULL needs N % 32 == 0); alpha [q][N] in; dy [T][N] `dtype` in; dx [T][K] `dtype` out. */
+bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
+                                const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Scale gradient (Eq. 4, read as the gradient of Eq. 2 with the empirical 1/g_L left to the caller):
+ *   dalpha[i][n] = grad_scale * sum_t dy[t][n] * sum_k B_i[n][k] * x[t][k]   for i < q_train.
+ * grad_scale = 1 gives the true gradient; the paper's damping is grad_scale = 1/K for row-wise scales.
+ * q_train = 1 is the paper's recipe (train alpha_1 only, Section 4.2); q_train = q trains all planes.
+ *   packed [q][N][K/32] in; x [T][K], dy [T][N] `dtype` in; dalpha [q_train][N] fp32 out, OVERWRITTEN.
+ * The result does not depend on the launch order of workgroups (no floating-point atomics). */
+bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCQ_H */

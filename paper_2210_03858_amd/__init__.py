@@ -1,0 +1,7 @@
+"""MI355X-native BCQ linear layer (AlphaTuning, arXiv 2210.03858): HIP kernels behind a C ABI.
+
+`binding` holds the thin ctypes layer over libbcq_hip.so; `synth` holds the seeded input generators.
+"""
+from . import synth  # noqa: F401
+from .binding import (BcqError, abi_version, bcq_linear_bwd_alpha, bcq_linear_bwd_input, bcq_linear_fwd,  # noqa: F401
+                      bcq_pack, bcq_pack_transposed, bcq_quantize, bcq_unpack, load, status_string, workspace_bytes)

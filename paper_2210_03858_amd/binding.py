@@ -1,0 +1,206 @@
+"""Thin ctypes binding of libbcq_hip.so (include/bcq.h): argument marshalling only.
+
+Every function takes torch tensors that live on the GPU (PyTorch is used for device memory and streams
+only), checks dtype/shape/contiguity on the host, passes raw device pointers and the current HIP stream to
+the C entry point of the same name, and raises BcqError on a non-zero status.  There is no CPU fallback:
+if the shared library is missing, load() raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbcq_hip.so")
+
+BCQ_F32, BCQ_BF16 = 0, 1
+OP_QUANTIZE, OP_FWD, OP_BWD_INPUT, OP_BWD_ALPHA = 0, 1, 2, 3
+QUANTIZE_MAX_K = 16384
+
+EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_quantize", "bcq_pack",
+           "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha")
+
+_lib = None
+
+
+class BcqError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        super().__init__("%s failed: status %d (%s)" % (what, self.status, status_string(self.status)))
+
+
+def load():
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s is missing: run `python -m paper_2210_03858_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no CPU fallback" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp, sz, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+    lib.bcq_status_string.restype = ctypes.c_char_p
+    lib.bcq_status_string.argtypes = [i32]
+    lib.bcq_abi_version.restype = i32
+    lib.bcq_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, ctypes.POINTER(sz)]
+    lib.bcq_quantize.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, sz, vp]
+    lib.bcq_pack.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.bcq_unpack.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.bcq_pack_transposed.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.bcq_linear_fwd.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.bcq_linear_bwd_input.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.bcq_linear_bwd_alpha.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, i32, f32, vp, vp, sz, vp]
+    for name in EXPORTS[2:]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load().bcq_status_string(int(status)).decode()
+
+
+def abi_version():
+    return int(load().bcq_abi_version())
+
+
+def workspace_bytes(op, T, N, K, q, dtype):
+    out = ctypes.c_size_t(0)
+    st = load().bcq_workspace_bytes(op, T, N, K, q, dtype, ctypes.byref(out))
+    if st:
+        raise BcqError(st, "bcq_workspace_bytes")
+    return int(out.value)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _need(t, dtype, shape, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype
+            and tuple(t.shape) == tuple(shape)):
+        raise ValueError("%s must be a contiguous cuda tensor of dtype %s and shape %s" % (name, dtype, tuple(shape)))
+
+
+def _act_dtype(t):
+    if t.dtype == torch.float32:
+        return BCQ_F32
+    if t.dtype == torch.bfloat16:
+        return BCQ_BF16
+    raise ValueError("activations must be float32 or bfloat16")
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous cuda tensor")
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _check(st, what):
+    if st:
+        raise BcqError(st, what)
+
+
+def bcq_quantize(W, q, alpha=None, packed=None, planes_i8=None, want_planes=False, workspace=None):
+    """Greedy BCQ of W[N,K] fp32 -> (alpha[q,N] f32, packed[q,N,K/32] int32 words, planes_i8 or None)."""
+    N, K = W.shape
+    _need(W, torch.float32, (N, K), "W")
+    dev = W.device
+    alpha = torch.empty((q, N), dtype=torch.float32, device=dev) if alpha is None else alpha
+    packed = torch.empty((q, N, K // 32), dtype=torch.int32, device=dev) if packed is None else packed
+    if planes_i8 is None and want_planes:
+        planes_i8 = torch.empty((q, N, K), dtype=torch.int8, device=dev)
+    _need(alpha, torch.float32, (q, N), "alpha")
+    _need(packed, torch.int32, (q, N, K // 32), "packed")
+    if planes_i8 is not None:
+        _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_quantize(_ptr(W), N, K, q, _ptr(alpha), _ptr(packed), _ptr(planes_i8), wp, wb, _stream()),
+           "bcq_quantize")
+    return alpha, packed, planes_i8
+
+
+def bcq_pack(planes_i8, packed=None):
+    q, N, K = planes_i8.shape
+    _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
+    packed = torch.empty((q, N, K // 32), dtype=torch.int32, device=planes_i8.device) if packed is None else packed
+    _need(packed, torch.int32, (q, N, K // 32), "packed")
+    _check(load().bcq_pack(_ptr(planes_i8), N, K, q, _ptr(packed), _stream()), "bcq_pack")
+    return packed
+
+
+def bcq_unpack(packed, planes_i8=None):
+    q, N, Kw = packed.shape
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    K = Kw * 32
+    planes_i8 = torch.empty((q, N, K), dtype=torch.int8, device=packed.device) if planes_i8 is None else planes_i8
+    _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
+    _check(load().bcq_unpack(_ptr(packed), N, K, q, _ptr(planes_i8), _stream()), "bcq_unpack")
+    return planes_i8
+
+
+def bcq_pack_transposed(packed, packed_t=None):
+    q, N, Kw = packed.shape
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    K = Kw * 32
+    if packed_t is None:
+        packed_t = torch.empty((q, K, max(N // 32, 1)), dtype=torch.int32, device=packed.device)
+    _check(load().bcq_pack_transposed(_ptr(packed), N, K, q, _ptr(packed_t), _stream()), "bcq_pack_transposed")
+    return packed_t
+
+
+def bcq_linear_fwd(packed, alpha, x, y=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    dt = _act_dtype(x)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N), "alpha")
+    _need(x, x.dtype, (T, K), "x")
+    y = torch.empty((T, N), dtype=x.dtype, device=x.device) if y is None else y
+    _need(y, x.dtype, (T, N), "y")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_fwd(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, q, _ptr(y), wp, wb, _stream()),
+           "bcq_linear_fwd")
+    return y
+
+
+def bcq_linear_bwd_input(packed, alpha, dy, packed_t=None, dx=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = dy.shape[0]
+    dt = _act_dtype(dy)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N), "alpha")
+    _need(dy, dy.dtype, (T, N), "dy")
+    if packed_t is not None:
+        _need(packed_t, torch.int32, (q, K, N // 32), "packed_t")
+    dx = torch.empty((T, K), dtype=dy.dtype, device=dy.device) if dx is None else dx
+    _need(dx, dy.dtype, (T, K), "dx")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_bwd_input(_ptr(packed), _ptr(packed_t), _ptr(alpha), _ptr(dy), dt, T, N, K, q,
+                                       _ptr(dx), wp, wb, _stream()), "bcq_linear_bwd_input")
+    return dx
+
+
+def bcq_linear_bwd_alpha(packed, x, dy, q_train=None, grad_scale=1.0, dalpha=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    dt = _act_dtype(x)
+    q_train = q if q_train is None else int(q_train)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(x, x.dtype, (T, K), "x")
+    _need(dy, x.dtype, (T, N), "dy")
+    dalpha = torch.empty((q_train, N), dtype=torch.float32, device=x.device) if dalpha is None else dalpha
+    _need(dalpha, torch.float32, (q_train, N), "dalpha")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_bwd_alpha(_ptr(packed), _ptr(x), _ptr(dy), dt, T, N, K, q, q_train,
+                                       float(grad_scale), _ptr(dalpha), wp, wb, _stream()), "bcq_linear_bwd_alpha")
+    return dalpha

@@ -1,0 +1,186 @@
+// C-ABI layer: argument validation, path selection, kernel enqueue.  See include/bcq.h for the contract.
+#include "../../include/bcq.h"
+
+#include "bcq_internal.h"
+
+#include <string.h>
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 17;      // N, K
+constexpr int64_t kMaxTokens = (int64_t)1 << 24;   // T
+constexpr int64_t kMaxElems = (int64_t)1 << 40;    // N*K, T*N, T*K
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+bcq_status check_shape(int64_t T, int64_t N, int64_t K, int q) {
+    if (N < 1 || K < 1 || T < 1 || q < 1 || q > 8) return BCQ_ERR_SHAPE;
+    if (K % 32 != 0) return BCQ_ERR_SHAPE;
+    if (N > kMaxDim || K > kMaxDim || T > kMaxTokens) return BCQ_ERR_SHAPE;
+    if (N * K > kMaxElems || T * N > kMaxElems || T * K > kMaxElems) return BCQ_ERR_SHAPE;
+    return BCQ_OK;
+}
+
+// One capability probe per device, cached: 1 = gfx950, 0 = anything else.
+bcq_status check_device() {
+    static int cache[64];  // 0 = unknown, 1 = ok, 2 = wrong
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return BCQ_ERR_DEVICE;
+    }
+    if (cache[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return BCQ_ERR_DEVICE;
+        }
+        cache[dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+    }
+    return cache[dev] == 1 ? BCQ_OK : BCQ_ERR_DEVICE;
+}
+
+inline bcq_status done(hipError_t e) { return e == hipSuccess ? BCQ_OK : BCQ_ERR_DEVICE; }
+
+bcq_status check_workspace(const void* ws, size_t have, size_t need) {
+    if (!ws) return BCQ_OK;
+    if (misaligned(ws)) return BCQ_ERR_ALIGN;
+    if (have < need) return BCQ_ERR_WORKSPACE;
+    return BCQ_OK;
+}
+
+size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype) {
+    (void)T; (void)N; (void)K; (void)q; (void)dtype;
+    switch (op) {
+        case BCQ_OP_QUANTIZE: return 16;  // status word
+        default: return 0;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* bcq_status_string(bcq_status s) {
+    switch (s) {
+        case BCQ_OK: return "ok";
+        case BCQ_ERR_NULL: return "a required pointer is NULL";
+        case BCQ_ERR_SHAPE: return "unsupported shape (need N,K,T >= 1, 1 <= q <= 8, K % 32 == 0, sizes within limits)";
+        case BCQ_ERR_DTYPE: return "unknown dtype or op code";
+        case BCQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case BCQ_ERR_WORKSPACE: return "workspace smaller than bcq_workspace_bytes()";
+        case BCQ_ERR_NONFINITE: return "non-finite weights";
+        case BCQ_ERR_DEVICE: return "no usable gfx950 device or HIP failure";
+    }
+    return "unknown status";
+}
+
+int bcq_abi_version(void) { return 1; }
+
+bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, int dtype, size_t* out) {
+    if (!out) return BCQ_ERR_NULL;
+    if (op < BCQ_OP_QUANTIZE || op > BCQ_OP_BWD_ALPHA) return BCQ_ERR_DTYPE;
+    if (op == BCQ_OP_QUANTIZE) T = 1;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    *out = workspace_need(op, T, N, K, q, dtype);
+    return BCQ_OK;
+}
+
+bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
+                        int8_t* planes_i8, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W || !alpha || !packed) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (K > BCQ_QUANTIZE_MAX_K) return BCQ_ERR_SHAPE;
+    if (misaligned(W) || misaligned(alpha) || misaligned(packed) || misaligned(planes_i8)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_QUANTIZE, 1, N, K, q, BCQ_F32));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_quantize(W, N, K, q, alpha, packed, planes_i8, (int*)workspace, (hipStream_t)stream));
+}
+
+bcq_status bcq_pack(const int8_t* planes_i8, int64_t N, int64_t K, int q, uint32_t* packed, void* stream) {
+    if (!planes_i8 || !packed) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (misaligned(planes_i8) || misaligned(packed)) return BCQ_ERR_ALIGN;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_pack(planes_i8, (int64_t)q * N * (K / 32), packed, (hipStream_t)stream));
+}
+
+bcq_status bcq_unpack(const uint32_t* packed, int64_t N, int64_t K, int q, int8_t* planes_i8, void* stream) {
+    if (!planes_i8 || !packed) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (misaligned(planes_i8) || misaligned(packed)) return BCQ_ERR_ALIGN;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_unpack(packed, (int64_t)q * N * (K / 32), planes_i8, (hipStream_t)stream));
+}
+
+bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* packed_t,
+                               void* stream) {
+    if (!packed || !packed_t) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (N % 32 != 0) return BCQ_ERR_SHAPE;
+    if (misaligned(packed) || misaligned(packed_t)) return BCQ_ERR_ALIGN;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_pack_transposed(packed, N, K, q, packed_t, (hipStream_t)stream));
+}
+
+bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                          int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    if (!packed || !alpha || !x || !y) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    if (misaligned(packed) || misaligned(alpha) || misaligned(x) || misaligned(y)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_FWD, T, N, K, q, dtype));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, q, y, (hipStream_t)stream));
+}
+
+bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
+                                const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (!packed || !alpha || !dy || !dx) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (packed_t && N % 32 != 0) return BCQ_ERR_SHAPE;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    if (misaligned(packed) || misaligned(packed_t) || misaligned(alpha) || misaligned(dy) || misaligned(dx))
+        return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_INPUT, T, N, K, q, dtype));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, q, dx, (hipStream_t)stream));
+}
+
+bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (!packed || !x || !dy || !dalpha) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (q_train < 1 || q_train > q) return BCQ_ERR_SHAPE;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    if (misaligned(packed) || misaligned(x) || misaligned(dy) || misaligned(dalpha)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_ALPHA, T, N, K, q, dtype));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, q, q_train, grad_scale, dalpha,
+                                              (hipStream_t)stream));
+}
+
+}  // extern "C"

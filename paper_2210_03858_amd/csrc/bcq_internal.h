@@ -1,0 +1,49 @@
+// Internal launch interface between the C-ABI layer (bcq_api.hip) and the gfx950 kernels.
+// Nothing here is exported; every function enqueues work on `st` and returns the HIP status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bcq {
+
+// ---- element helpers shared by all kernels -------------------------------------------------
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round to nearest even; NaN stays NaN (quiet)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename XT> struct Elem;
+template <> struct Elem<float> {
+    __device__ static __forceinline__ float load(const float* p) { return *p; }
+    __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+    __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- one-time kernels -----------------------------------------------------------------------
+hipError_t launch_pack(const int8_t* planes, int64_t total_words, uint32_t* packed, hipStream_t st);
+hipError_t launch_unpack(const uint32_t* packed, int64_t total_words, int8_t* planes, hipStream_t st);
+hipError_t launch_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* packed_t,
+                                  hipStream_t st);
+hipError_t launch_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
+                           int8_t* planes, int* status_word, hipStream_t st);
+
+// ---- any-shape kernels (plain vector ALU; need no workspace) --------------------------------
+hipError_t launch_fwd_generic(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                              int64_t N, int64_t K, int q, void* y, hipStream_t st);
+hipError_t launch_bwd_input_generic(const uint32_t* packed, const float* alpha, const void* dy, int dtype,
+                                    int64_t T, int64_t N, int64_t K, int q, void* dx, hipStream_t st);
+hipError_t launch_bwd_alpha_generic(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                    int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
+                                    hipStream_t st);
+
+}  // namespace bcq

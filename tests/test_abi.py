@@ -1,0 +1,102 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every symbol the header
+declares, and every argument error is reported before any device is touched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2210_03858_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "bcq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bcq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared_functions()
+    assert {"bcq_quantize", "bcq_pack", "bcq_unpack", "bcq_linear_fwd", "bcq_linear_bwd_input",
+            "bcq_linear_bwd_alpha", "bcq_workspace_bytes", "bcq_status_string"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    from paper_2210_03858_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(8):
+        s = lib.bcq_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.bcq_abi_version() >= 1
+
+
+A = 0x1000  # a fake, aligned, never dereferenced pointer
+
+
+def test_workspace_bytes_validation(lib):
+    out = ctypes.c_size_t(123)
+    assert lib.bcq_workspace_bytes(1, 8, 64, 64, 3, 1, None) == 1
+    assert lib.bcq_workspace_bytes(9, 8, 64, 64, 3, 1, ctypes.byref(out)) == 3
+    assert lib.bcq_workspace_bytes(1, 8, 64, 48, 3, 1, ctypes.byref(out)) == 2
+    assert lib.bcq_workspace_bytes(1, 8, 64, 64, 9, 1, ctypes.byref(out)) == 2
+    assert lib.bcq_workspace_bytes(1, 8, 64, 64, 3, 7, ctypes.byref(out)) == 3
+    assert lib.bcq_workspace_bytes(0, 0, 64, 64, 3, 0, ctypes.byref(out)) == 0  # T ignored for quantize
+    assert out.value >= 16
+
+
+def test_argument_errors_before_device(lib):
+    q, N, K, T = 3, 64, 64, 8
+    # NULL
+    assert lib.bcq_quantize(None, N, K, q, A, A, None, None, 0, None) == 1
+    assert lib.bcq_pack(None, N, K, q, A, None) == 1
+    assert lib.bcq_unpack(A, N, K, q, None, None) == 1
+    assert lib.bcq_pack_transposed(A, N, K, q, None, None) == 1
+    assert lib.bcq_linear_fwd(A, None, A, 1, T, N, K, q, A, None, 0, None) == 1
+    assert lib.bcq_linear_bwd_input(A, None, A, None, 1, T, N, K, q, A, None, 0, None) == 1
+    assert lib.bcq_linear_bwd_alpha(A, A, A, 1, T, N, K, q, q, 1.0, None, None, 0, None) == 1
+    # shape
+    assert lib.bcq_quantize(A, N, 40, q, A, A, None, None, 0, None) == 2
+    assert lib.bcq_quantize(A, N, 16384 + 32, q, A, A, None, None, 0, None) == 2
+    assert lib.bcq_pack(A, 0, K, q, A, None) == 2
+    assert lib.bcq_linear_fwd(A, A, A, 1, 0, N, K, q, A, None, 0, None) == 2
+    assert lib.bcq_linear_fwd(A, A, A, 1, T, N, K, 0, A, None, 0, None) == 2
+    assert lib.bcq_linear_bwd_input(A, A, A, A, 1, T, 48, K, q, A, None, 0, None) == 2  # twin needs N % 32 == 0
+    assert lib.bcq_pack_transposed(A, 48, K, q, A, None) == 2
+    assert lib.bcq_linear_bwd_alpha(A, A, A, 1, T, N, K, q, q + 1, 1.0, A, None, 0, None) == 2
+    assert lib.bcq_linear_bwd_alpha(A, A, A, 1, T, N, K, q, 0, 1.0, A, None, 0, None) == 2
+    # dtype
+    assert lib.bcq_linear_fwd(A, A, A, 2, T, N, K, q, A, None, 0, None) == 3
+    assert lib.bcq_linear_bwd_input(A, None, A, A, -1, T, N, K, q, A, None, 0, None) == 3
+    # alignment
+    assert lib.bcq_linear_fwd(A + 4, A, A, 1, T, N, K, q, A, None, 0, None) == 4
+    assert lib.bcq_linear_fwd(A, A, A, 1, T, N, K, q, A, A + 8, 1 << 20, None) == 4
+    assert lib.bcq_quantize(A, N, K, q, A, A, A + 1, None, 0, None) == 4
+    # workspace too small
+    assert lib.bcq_quantize(A, N, K, q, A, A, None, A, 4, None) == 5
+
+
+def test_no_device_is_reported(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    assert lib.bcq_linear_fwd(A, A, A, 1, 8, 64, 64, 3, A, None, 0, None) == 7
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    from paper_2210_03858_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libbcq_hip.so")
+    with pytest.raises(RuntimeError):
+        binding.load()

@@ -1,0 +1,200 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on seeded inputs.
+
+Bar: sign planes, packed words and the transposed twin bit-exact; floating-point outputs within the
+normalised max-abs error of _util (1e-5 for fp32 activations, 2e-2 for bf16 activations).
+"""
+import numpy as np
+import pytest
+
+from _util import (make_case, nmax_err, packed_to_dev, packed_to_host, to_dev, to_host, tol_for)
+from paper_2210_03858_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bcq():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2210_03858_amd as p
+    p.load()
+    return p
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ pack / unpack / transposed twin
+
+@pytest.mark.parametrize("q,N,K", [(1, 1, 32), (3, 5, 96), (2, 67, 1280), (4, 1024, 1024), (1, 300, 4096)])
+def test_pack_unpack_bit_exact(bcq, oracle, q, N, K):
+    rng = np.random.default_rng(100 + N + K)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    packed_ref = oracle.pack(planes)
+    import torch
+    d_planes = torch.from_numpy(planes).cuda()
+    d_packed = bcq.bcq_pack(d_planes)
+    _sync()
+    assert np.array_equal(packed_to_host(d_packed), packed_ref)
+    back = bcq.bcq_unpack(d_packed)
+    _sync()
+    assert np.array_equal(back.cpu().numpy(), planes)
+    # only the sign of the byte counts
+    odd = planes.astype(np.int16) * rng.integers(1, 128, size=planes.shape)
+    odd[planes > 0] -= 1  # includes 0 -> +1
+    d_packed2 = bcq.bcq_pack(torch.from_numpy(odd.astype(np.int8)).cuda())
+    _sync()
+    assert np.array_equal(packed_to_host(d_packed2), packed_ref)
+
+
+@pytest.mark.parametrize("q,N,K", [(1, 32, 32), (3, 96, 160), (2, 1280, 5120), (4, 1024 + 32, 1024)])
+def test_pack_transposed_bit_exact(bcq, oracle, q, N, K):
+    rng = np.random.default_rng(200 + N + K)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    twin_ref = oracle.pack(np.ascontiguousarray(planes.transpose(0, 2, 1)))  # bits along N
+    d_twin = bcq.bcq_pack_transposed(packed_to_dev(oracle.pack(planes)))
+    _sync()
+    assert np.array_equal(packed_to_host(d_twin), twin_ref)
+
+
+# ------------------------------------------------------------------ greedy quantizer
+
+def _check_quantize(bcq, oracle, W, q, want_planes=True):
+    import torch
+    a_ref, b_ref, margin = oracle.quantize(W, q, with_margin=True)
+    ws = torch.full((4,), 77, dtype=torch.int32, device="cuda")
+    alpha, packed, planes = bcq.bcq_quantize(to_dev(W), q, want_planes=want_planes, workspace=ws)
+    _sync()
+    assert int(ws[0].item()) == 0
+    alpha, packed = alpha.cpu().numpy(), packed_to_host(packed)
+    planes_gpu = oracle.unpack(packed, W.shape[1])
+    if want_planes:
+        assert np.array_equal(planes.cpu().numpy(), planes_gpu)
+    # rows where some fp64 mean sits on an fp32 rounding boundary may legitimately round either way
+    fragile = (margin < 2.0 ** -40).any(axis=0)
+    ok = ~fragile
+    assert fragile.sum() <= max(1, W.shape[0] // 1000)
+    assert np.array_equal(alpha[:, ok].view(np.uint32), a_ref[:, ok].view(np.uint32))
+    assert np.array_equal(planes_gpu[:, ok], b_ref[:, ok])
+    assert np.array_equal(packed[:, ok], oracle.pack(b_ref)[:, ok])
+    for n in np.nonzero(fragile)[0]:
+        for i in range(q):
+            assert abs(float(alpha[i, n]) - float(a_ref[i, n])) <= np.spacing(a_ref[i, n]) or i > 0
+        a_forced, b_forced = oracle.quantize_row_forced(W[n], q, alpha[:, n], np.ones(q, np.uint8))
+        assert np.array_equal(b_forced, planes_gpu[:, n])
+
+
+@pytest.mark.parametrize("q,N,K", [(3, 1024, 1024), (1, 8, 32), (4, 37, 1280), (2, 16, 96), (4, 64, 10240),
+                                   (3, 9, 16384), (4, 200, 2560 + 32)])
+def test_quantize_bit_exact(bcq, oracle, q, N, K):
+    W = synth.weights(1, "out", N, K, extra=K)
+    _check_quantize(bcq, oracle, W, q)
+
+
+def test_quantize_outliers_zero_rows_no_planes(bcq, oracle):
+    W = synth.weights(4, "qkv", 2048, 2048, outliers=True)
+    W[5] = 0.0
+    W[6, ::2] = 0.0
+    W[7, :3] = [-0.0, 0.0, 1.0]
+    _check_quantize(bcq, oracle, W, 3, want_planes=False)
+
+
+def test_quantize_reports_nonfinite_rows(bcq):
+    import torch
+    W = synth.weights(1, "out", 64, 256)
+    W[3, 7] = np.inf
+    W[40, 0] = np.nan
+    ws = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    bcq.bcq_quantize(to_dev(W), 2, workspace=ws)
+    _sync()
+    assert int(ws[0].item()) == 2
+
+
+# ------------------------------------------------------------------ forward / backward, full comparison
+
+def _run_layer(bcq, oracle, config, kind, T, N, K, q, dtype, outliers=False, q_train=None, grad_scale=1.0,
+               twin=True, workspace=False):
+    import torch
+    W, alpha, planes, packed, x, dy = make_case(config, kind, T, N, K, q, dtype, oracle, outliers)
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha)
+    d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
+    d_twin = bcq.bcq_pack_transposed(d_packed) if (twin and N % 32 == 0) else None
+    code = 0 if dtype == "f32" else 1
+
+    def ws(op):
+        if not workspace:
+            return None
+        nbytes = bcq.workspace_bytes(op, T, N, K, q, code)
+        return torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+
+    y = bcq.bcq_linear_fwd(d_packed, d_alpha, d_x, workspace=ws(1))
+    dx = bcq.bcq_linear_bwd_input(d_packed, d_alpha, d_dy, packed_t=d_twin, workspace=ws(2))
+    da = bcq.bcq_linear_bwd_alpha(d_packed, d_x, d_dy, q_train=q_train, grad_scale=grad_scale, workspace=ws(3))
+    _sync()
+    tol = tol_for(dtype)
+    e_y = nmax_err(to_host(y), oracle.fwd(alpha, planes, x))
+    e_dx = nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy))
+    e_da = nmax_err(to_host(da), oracle.bwd_alpha(planes, x, dy, q_train=q_train, grad_scale=grad_scale))
+    assert e_y <= tol, ("fwd", e_y)
+    assert e_dx <= tol, ("bwd_input", e_dx)
+    assert e_da <= tol, ("bwd_alpha", e_da)
+    return e_y, e_dx, e_da
+
+
+def test_config1_fp32_full(bcq, oracle):
+    """N = K = 1024, q = 3, 32 fp32 tokens: quantize on the GPU, then fwd + dx + dalpha against the oracle."""
+    import torch
+    cfg = synth.CONFIGS[1]
+    N, K = synth.layer_shape(cfg["h"], "out")
+    T, q = cfg["tokens"][0], cfg["q"][0]
+    W = synth.weights(1, "out", N, K)
+    _check_quantize(bcq, oracle, W, q)
+    for workspace in (False, True):
+        _run_layer(bcq, oracle, 1, "out", T, N, K, q, "f32", workspace=workspace)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,N,K,q", [(1, 64, 64, 1), (4, 1280, 1280, 2), (8, 96, 160, 3), (33, 300, 416, 4),
+                                     (300, 544, 1056, 3), (17, 35, 32, 8)])
+def test_small_shapes_ragged(bcq, oracle, dtype, T, N, K, q):
+    """Shapes that span several tiles with ragged tails in T, N and K; with and without workspace / twin."""
+    for workspace, twin in ((False, False), (True, True)):
+        _run_layer(bcq, oracle, 3, "out", T, N, K, q, dtype, workspace=workspace, twin=twin)
+
+
+def test_q_train_and_grad_scale(bcq, oracle):
+    _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "bf16", q_train=1, grad_scale=1.0 / 512, workspace=True)
+    _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "f32", q_train=2, grad_scale=0.5)
+
+
+def test_fp32_integer_case_is_exact(bcq, oracle):
+    """Small-integer activations and power-of-two scales: every partial sum is exact in fp32, so the fp32
+    path must reproduce the oracle exactly (zero tolerance catches any indexing slip)."""
+    rng = np.random.default_rng(7)
+    T, N, K, q = 19, 160, 224, 3
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    alpha = np.ldexp(1.0, rng.integers(-3, 3, size=(q, N))).astype(np.float32)
+    x = rng.integers(-8, 9, size=(T, K)).astype(np.float32)
+    dy = rng.integers(-4, 5, size=(T, N)).astype(np.float32)
+    d_packed = packed_to_dev(oracle.pack(planes))
+    y = bcq.bcq_linear_fwd(d_packed, to_dev(alpha), to_dev(x))
+    dx = bcq.bcq_linear_bwd_input(d_packed, to_dev(alpha), to_dev(dy))
+    da = bcq.bcq_linear_bwd_alpha(d_packed, to_dev(x), to_dev(dy))
+    _sync()
+    assert np.array_equal(to_host(y).astype(np.float64), oracle.fwd(alpha, planes, x))
+    assert np.array_equal(to_host(dx).astype(np.float64), oracle.bwd_input(alpha, planes, dy))
+    assert np.array_equal(to_host(da).astype(np.float64), oracle.bwd_alpha(planes, x, dy))
+
+
+def test_bwd_alpha_is_deterministic(bcq, oracle):
+    import torch
+    W, alpha, planes, packed, x, dy = make_case(2, "qkv", 512, 768, 1024, 4, "bf16", oracle)
+    d_packed, d_x, d_dy = packed_to_dev(packed), to_dev(x, "bf16"), to_dev(dy, "bf16")
+    nbytes = bcq.workspace_bytes(3, 512, 768, 1024, 4, 1)
+    ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+    a = bcq.bcq_linear_bwd_alpha(d_packed, d_x, d_dy, workspace=ws).clone()
+    b = bcq.bcq_linear_bwd_alpha(d_packed, d_x, d_dy, workspace=ws)
+    _sync()
+    assert torch.equal(a.view(torch.int32), b.view(torch.int32))
