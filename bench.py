@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the BCQ linear hot path on one MI355X.
+
+Workload (default): the four linear layers of one GPT-2-medium-shaped block (h = 1024: QKV 1024->3072,
+out 1024->1024, MLP 1024->4096->1024), q = 4 bit planes, bf16 activations, T = 8 x 512 = 4096 tokens,
+W ~ N(0, 0.02^2) quantized once by the greedy quantizer, x, dy ~ N(0, 1).  One step = forward, input gradient
+and alpha gradient of all four layers.  The quantizer, pack and transposed-twin passes run once before the
+timed region (they are the one-time PTQ of the method) and are timed separately in "setup".
+
+Prints ONE JSON line: effective TFLOP/s (6 T N K flops per layer and step), the roofline figures of the
+dominant kernel family measured with HIP events inside the timed region, and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload number (2 = GPT-2-medium block, the headline)")
+    ap.add_argument("--tokens", type=int, default=0, help="override the token count of the workload")
+    ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are part of "
+              "the BCQ linear hot path; see DESIGN.md for how it would shard)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2210_03858_amd as bcq
+    from paper_2210_03858_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    bcq.load()
+
+    cfg = synth.CONFIGS[args.config]
+    h = cfg["h"]
+    q = args.q or cfg["q"][-1]
+    T = args.tokens or cfg["tokens"][-1]
+    dtype = cfg["dtype"]
+    tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = bcq.binding.BCQ_BF16 if dtype == "bf16" else bcq.binding.BCQ_F32
+    kinds = cfg["kinds"]
+
+    # ---------------- one-time setup: synthetic weights -> greedy BCQ on the GPU, twin, activations
+    layers = []
+    setup_ms = {"quantize": 0.0, "pack_transposed": 0.0}
+    weights_total = 0
+    for kind in kinds:
+        N, K = synth.layer_shape(h, kind)
+        W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])).cuda()
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        bcq.bcq_quantize(W, q)  # warm
+        e0.record()
+        alpha, packed, _ = bcq.bcq_quantize(W, q)
+        e1.record()
+        twin = bcq.bcq_pack_transposed(packed) if N % 32 == 0 else None
+        e2.record()
+        torch.cuda.synchronize()
+        setup_ms["quantize"] += e0.elapsed_time(e1)
+        setup_ms["pack_transposed"] += e1.elapsed_time(e2)
+        weights_total += N * K
+        x = torch.from_numpy(synth.activations(args.config, kind, T, K, 1, dtype)).cuda().to(tdtype)
+        dy = torch.from_numpy(synth.activations(args.config, kind, T, N, 2, dtype)).cuda().to(tdtype)
+        ws = {}
+        for op in (1, 2, 3):
+            nbytes = bcq.workspace_bytes(op, T, N, K, q, code)
+            ws[op] = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+        layers.append(dict(kind=kind, N=N, K=K, alpha=alpha, packed=packed, twin=twin, x=x, dy=dy, ws=ws,
+                           y=torch.empty((T, N), dtype=tdtype, device="cuda"),
+                           dx=torch.empty((T, K), dtype=tdtype, device="cuda"),
+                           da=torch.empty((q, N), dtype=torch.float32, device="cuda")))
+        del W
+
+    ops = ("fwd", "bwd_input", "bwd_alpha")
+
+    def run_op(L, op):
+        if op == "fwd":
+            bcq.bcq_linear_fwd(L["packed"], L["alpha"], L["x"], y=L["y"], workspace=L["ws"][1])
+        elif op == "bwd_input":
+            bcq.bcq_linear_bwd_input(L["packed"], L["alpha"], L["dy"], packed_t=L["twin"], dx=L["dx"],
+                                     workspace=L["ws"][2])
+        else:
+            bcq.bcq_linear_bwd_alpha(L["packed"], L["x"], L["dy"], dalpha=L["da"], workspace=L["ws"][3])
+
+    def step(events=None):
+        for L in layers:
+            for op in ops:
+                if events is not None:
+                    a = torch.cuda.Event(enable_timing=True)
+                    b = torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    run_op(L, op)
+                    b.record()
+                    events.append((op, L["kind"], a, b))
+                else:
+                    run_op(L, op)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---------------- timed region: exactly --steps steps
+    events = None if args.no_events else []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    flops_layer = {L["kind"]: 2.0 * T * L["N"] * L["K"] for L in layers}
+    flops_step = 3.0 * sum(flops_layer.values())
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---------------- per-op timing -> dominant kernel family and its roofline
+    per_op = {}
+    roofline = None
+    if events:
+        for op, kind, a, b in events:
+            d = per_op.setdefault(op, dict(ms=0.0, launches=0, flops=0.0))
+            d["ms"] += a.elapsed_time(b)
+            d["launches"] += 1
+            d["flops"] += flops_layer[kind]
+        dom = max(per_op, key=lambda k: per_op[k]["ms"])
+        d = per_op[dom]
+        achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "bcq_linear_" + dom, "achieved": round(achieved, 3),
+                    "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
+                    "traffic": None, "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
+                    "launches": d["launches"],
+                    "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
+        per_op = {k: {"ms_per_step": round(v["ms"] / args.steps, 4),
+                      "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3)} for k, v in per_op.items()}
+
+    # ---------------- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import bcq_oracle as oracle
+        kind = "out"
+        N, K = synth.layer_shape(h, kind)
+        Ts = min(T, 128)
+        W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
+        a_ref, planes_ref = oracle.quantize(W, q)
+        xs = synth.activations(args.config, kind, T, K, 1, dtype)[:Ts]
+        dys = synth.activations(args.config, kind, T, N, 2, dtype)[:Ts]
+        c0 = time.perf_counter()
+        oracle.fwd(a_ref, planes_ref, xs)
+        oracle.bwd_input(a_ref, planes_ref, dys)
+        oracle.bwd_alpha(planes_ref, xs, dys)
+        c1 = time.perf_counter()
+        cpu = {"value": round(6.0 * Ts * N * K / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(c1 - c0, 2),
+               "sample": "fwd+dx+dalpha of the %dx%d '%s' layer, q=%d, first %d of %d tokens, fp64 naive loops"
+                         % (N, K, kind, q, Ts, T)}
+
+    out = {
+        "metric": "BCQ linear fwd+bwd effective TFLOP/s",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dtype,
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s activations, T=%d tokens; fwd+dx+dalpha"
+                               % (args.config, h, "/".join(kinds), q, dtype, T),
+                   "h": h, "q": q, "tokens": T, "weights_per_block": weights_total},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "per_op": per_op,
+        "setup": {k: round(v, 4) for k, v in setup_ms.items()},
+        "packed_weight_bytes": q * weights_total // 8,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

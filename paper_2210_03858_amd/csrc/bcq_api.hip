@@ -49,10 +49,20 @@ bcq_status check_workspace(const void* ws, size_t have, size_t need) {
     return BCQ_OK;
 }
 
+// Token count from which the tiled matrix-core kernels are used (bf16 activations, workspace given).
+constexpr int64_t kMfmaMinTokens = 32;
+
+bool mfma_fwd_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T >= kMfmaMinTokens; }
+bool mfma_bwd_input_ok(int64_t T, int64_t N, int dtype) {
+    return dtype == BCQ_BF16 && T >= kMfmaMinTokens && N % 8 == 0;  // rows of dy must be 16-byte aligned
+}
+
 size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype) {
-    (void)T; (void)N; (void)K; (void)q; (void)dtype;
+    (void)q;
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
+        case BCQ_OP_FWD: return mfma_fwd_ok(T, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
+        case BCQ_OP_BWD_INPUT: return mfma_bwd_input_ok(T, N, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
         default: return 0;
     }
 }
@@ -146,6 +156,8 @@ bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (workspace && mfma_fwd_ok(T, dtype))
+        return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, q, y, workspace, (hipStream_t)stream));
     return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, q, y, (hipStream_t)stream));
 }
 
@@ -163,6 +175,8 @@ bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (workspace && mfma_bwd_input_ok(T, N, dtype))
+        return done(bcq::launch_bwd_input_mfma(packed, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
     return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, q, dx, (hipStream_t)stream));
 }
 
