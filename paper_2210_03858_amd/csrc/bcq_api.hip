@@ -57,12 +57,18 @@ bool mfma_bwd_input_ok(int64_t T, int64_t N, int dtype) {
     return dtype == BCQ_BF16 && T >= kMfmaMinTokens && N % 8 == 0;  // rows of dy must be 16-byte aligned
 }
 
+bool mfma_bwd_alpha_ok(int64_t T, int64_t N, int64_t K, int dtype) {
+    (void)K;
+    return dtype == BCQ_BF16 && T >= 64 && N % 8 == 0 && N >= 8;  // rows of dy 16-byte aligned
+}
+
 size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype) {
     (void)q;
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
         case BCQ_OP_FWD: return mfma_fwd_ok(T, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
         case BCQ_OP_BWD_INPUT: return mfma_bwd_input_ok(T, N, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
+        case BCQ_OP_BWD_ALPHA: return mfma_bwd_alpha_ok(T, N, K, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, q) : 0;
         default: return 0;
     }
 }
@@ -193,6 +199,9 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (workspace && mfma_bwd_alpha_ok(T, N, K, dtype))
+        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, q_train, grad_scale, dalpha, workspace,
+                                               (hipStream_t)stream));
     return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, q, q_train, grad_scale, dalpha,
                                               (hipStream_t)stream));
 }
