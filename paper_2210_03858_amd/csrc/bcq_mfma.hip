@@ -27,6 +27,14 @@ constexpr int ROWB = BK * 2 + 16;         // bytes per LDS row of the activation
 constexpr int STAGE = BM * ROWB;          // bytes per LDS stage
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+// two fp32 -> two bf16 (round to nearest even) in one v_cvt_pk_bf16_f32; `lo` lands in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -65,7 +73,7 @@ __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restr
                 if (i < q) s += ((bits[i] >> j) & 1u) ? a[i] : -a[i];
             v[e] = s;
         }
-        out[p] = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+        out[p] = pack_bf16x2(v[0], v[1]);
     }
     frag[(ct * R16 + (slot >> 1)) * 64 + c + 32 * (int)(slot & 1)] = make_uint4(out[0], out[1], out[2], out[3]);
 }
@@ -103,7 +111,7 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
             }
             v[e] = s;
         }
-        out[p] = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+        out[p] = pack_bf16x2(v[0], v[1]);
     }
     frag[(ct * R16 + ks) * 64 + c + 32 * g] = make_uint4(out[0], out[1], out[2], out[3]);
 }
@@ -111,13 +119,26 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
 // ---------------------------------------------------------------------------------------------------------
 // C[M][NC] = A[M][R] * Bfrag, A row-major bf16 with leading dimension lda, Bfrag in fragment order with R16
 // slices per column tile (R16 * 16 >= R, a multiple of BK), C row-major bf16 with leading dimension ldc.
+// Workgroup tile (64 TM) x (64 TN), 4 waves in a 2 x 2 grid, each wave TM x TN MFMA tiles.
 // The weight fragment is the first MFMA operand, so one lane ends up with 4 consecutive output columns of
-// one token (8-byte stores).  Out-of-range rows, chunks and column tiles are clamped to valid addresses
-// instead of branching: their products land in outputs that are never stored, or meet zero weights.
-__global__ __launch_bounds__(256, 1) void gemm_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                      const u32x4* __restrict__ Bfrag, bf16_t* __restrict__ C,
-                                                      int64_t ldc, int64_t M, int64_t NC, int64_t R, int64_t R16,
-                                                      int tiles_m, int tiles_n) {
+// one token.  Out-of-range rows, chunks and column tiles are clamped to valid addresses instead of branching:
+// their products land in outputs that are never stored, or meet zero weights.
+template <int TM, int TN>
+struct GemmCfg {
+    static constexpr int BMT = 64 * TM, BNT = 64 * TN;
+    static constexpr int STAGE_B = BMT * ROWB;                 // one activation stage
+    static constexpr int EPI_ROWB = 64 * TN + 8;               // epilogue row: 32 TN columns of bf16 + pad
+    static constexpr int EPI_B = 4 * 64 * EPI_ROWB;            // 4 waves x 64 tokens
+    static constexpr int LDS_B = (2 * STAGE_B > EPI_B) ? 2 * STAGE_B : EPI_B;
+    static constexpr int OCC = (TM * TN >= 16) ? 1 : 2;
+};
+
+template <int TM, int TN>
+__global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
+    const bf16_t* __restrict__ A, int64_t lda, const u32x4* __restrict__ Bfrag, bf16_t* __restrict__ C, int64_t ldc,
+    int64_t M, int64_t NC, int64_t R, int64_t R16, int tiles_m, int tiles_n) {
+    using Cfg = GemmCfg<TM, TN>;
+    constexpr int STAGE_B = Cfg::STAGE_B;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -129,75 +150,83 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const bf16_t* __restrict__
     const int per_xcd = total / 8;
     const int lid = (bid < per_xcd * 8) ? (bid % 8) * per_xcd + bid / 8 : bid;
     const int tile_n = lid / tiles_m, tile_m = lid % tiles_m;
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int64_t m0 = (int64_t)tile_m * Cfg::BMT, n0 = (int64_t)tile_n * Cfg::BNT;
     const int64_t ct_count = (NC + 31) / 32;
 
-    f32x16 acc[4][4];  // [weight tile][token tile]
+    f32x16 acc[TN][TM];  // [weight tile][token tile]
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // activation tile: 256 rows x 8 chunks of 16 B; thread handles chunk lc of rows lr + 32 * j
+    // activation tile: 64 TM rows x 8 chunks of 16 B; thread handles chunk lc of rows lr + 32 * j
+    constexpr int NA = 2 * TM;
     const int lc = tid & 7, lr = tid >> 3;
-    const bf16_t* arow[8];
+    const bf16_t* arow[NA];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < NA; ++j) {
         int64_t row = m0 + lr + 32 * j;
         row = row < M ? row : M - 1;
         arow[j] = A + row * lda;
     }
     const int64_t kmax = R - 8;
-    u32x4 areg[8];
+    u32x4 areg[NA];
     auto load_a = [&](int64_t k0) {
+#ifdef BCQ_PROBE_NO_A
+        if (k0 > 0) return;
+#endif
         int64_t k = k0 + lc * 8;
         k = k < kmax ? k : kmax;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) areg[j] = *reinterpret_cast<const u32x4*>(arow[j] + k);
+        for (int j = 0; j < NA; ++j) areg[j] = *reinterpret_cast<const u32x4*>(arow[j] + k);
     };
     auto store_a = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            *reinterpret_cast<u32x4*>(smem + buf * STAGE + (lr + 32 * j) * ROWB + lc * 16) = areg[j];
+        for (int j = 0; j < NA; ++j)
+            *reinterpret_cast<u32x4*>(smem + buf * STAGE_B + (lr + 32 * j) * ROWB + lc * 16) = areg[j];
     };
 
-    // weight fragments of this wave: column tiles ct0 .. ct0+3
-    const int64_t ct0 = (n0 + wn * 128) / 32;
-    const u32x4* bptr[4];
+    // weight fragments of this wave: column tiles ct0 .. ct0+TN-1
+    const int64_t ct0 = (n0 + wn * 32 * TN) / 32;
+    const u32x4* bptr[TN];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < TN; ++j) {
         int64_t ct = ct0 + j;
         ct = ct < ct_count ? ct : ct_count - 1;
         bptr[j] = Bfrag + ct * R16 * 64 + lane;
     }
-    u32x4 b[4][4];  // [kk][j]; slot kk is refilled for the next K-step right after its MFMAs are issued
+    u32x4 b[4][TN];  // [kk][j]; slot kk is refilled for the next K-step right after its MFMAs are issued
     auto load_b = [&](int kk, int64_t step) {
+#ifdef BCQ_PROBE_NO_B
+        if (step > 0) return;
+#endif
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b[kk][j] = bptr[j][(step * 4 + kk) * 64];
+        for (int j = 0; j < TN; ++j) b[kk][j] = bptr[j][(step * 4 + kk) * 64];
     };
-    bf16x8 xf[2][4];  // activation fragments of two consecutive 16-slices
+    bf16x8 xf[2][TM];  // activation fragments of two consecutive 16-slices
     auto read_x = [&](int buf, int kk) {
-        const unsigned char* sa = smem + buf * STAGE + (wm * 128 + (lane & 31)) * ROWB + (lane >> 5) * 16 + kk * 32;
+        const unsigned char* sa =
+            smem + buf * STAGE_B + (wm * 32 * TM + (lane & 31)) * ROWB + (lane >> 5) * 16 + kk * 32;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWB);
+        for (int i = 0; i < TM; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWB);
     };
     auto compute = [&](int buf, int64_t next_step) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) read_x(buf, kk + 1);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < TM; ++i)
                     acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), xf[kk & 1][i], acc[j][i],
                                                                         0, 0, 0);
             load_b(kk, next_step);
-            // issue order inside the slice: LDS reads of the next slice, the 16 MFMAs, then the weight refill
-            if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
+            // issue order inside the slice: LDS reads of the next slice, the MFMAs, then the weight refill
+            if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, TM, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -223,29 +252,75 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const bf16_t* __restrict__
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    // epilogue: acc register 4g+e of lane l is weight column 8g + 4*(l/32) + e, token l%32 of its 32 x 32 tile
-    const bool vec_ok = (ldc % 4 == 0);
+    // epilogue: acc register 4g+e of lane l is weight column 8g + 4*(l/32) + e, token l%32 of its 32 x 32 tile.
+    // Pass the tile through LDS (64 tokens per wave at a time) so that global stores are 16 B per lane and
+    // whole rows of 64 TN bytes are contiguous.
+    constexpr int EROW = Cfg::EPI_ROWB;
+#ifdef BCQ_PROBE_NO_STORE
+    if (acc[0][0][0] != 123.456f) return;
+#endif
+    const bool vec_ok = (ldc % 8 == 0);
+    if (vec_ok) {
+        unsigned char* ew = smem + wave * 64 * EROW;
+        constexpr int CH = 4 * TN;        // 16-byte chunks per row
+        constexpr int RPI = 64 / CH;      // rows per store instruction
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int64_t t = m0 + wm * 128 + it * 32 + (lane & 31);
-        if (t >= M) continue;
-        bf16_t* crow = C + t * ldc;
+        for (int pass = 0; pass < (TM + 1) / 2; ++pass) {
+            __syncthreads();
 #pragma unroll
-        for (int jw = 0; jw < 4; ++jw)
+            for (int il = 0; il < 2; ++il) {
+                const int it = pass * 2 + il;
+                if (it < TM) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int64_t n = n0 + wn * 128 + jw * 32 + 8 * g + 4 * (lane >> 5);
-                if (vec_ok && n + 3 < NC) {
-                    uint2 o;
-                    o.x = (uint32_t)f32_to_bf16(acc[jw][it][4 * g]) | ((uint32_t)f32_to_bf16(acc[jw][it][4 * g + 1]) << 16);
-                    o.y = (uint32_t)f32_to_bf16(acc[jw][it][4 * g + 2]) | ((uint32_t)f32_to_bf16(acc[jw][it][4 * g + 3]) << 16);
-                    *reinterpret_cast<uint2*>(crow + n) = o;
-                } else {
+                    for (int jw = 0; jw < TN; ++jw)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            uint2 o;
+                            o.x = pack_bf16x2(acc[jw][it][4 * g], acc[jw][it][4 * g + 1]);
+                            o.y = pack_bf16x2(acc[jw][it][4 * g + 2], acc[jw][it][4 * g + 3]);
+                            *reinterpret_cast<uint2*>(ew + (il * 32 + (lane & 31)) * EROW +
+                                                      (jw * 32 + 8 * g + 4 * (lane >> 5)) * 2) = o;
+                        }
+                }
+            }
+            __syncthreads();
+            const int rows_here = (TM - pass * 2 >= 2) ? 64 : 32;
+            const int ch = lane % CH, r0 = lane / CH;
+#pragma unroll
+            for (int rr = 0; rr < 64 / RPI; ++rr) {
+                const int r = rr * RPI + r0;
+                if (r < rows_here) {
+                    const int64_t t = m0 + wm * 32 * TM + pass * 64 + r;
+                    const int64_t n = n0 + wn * 32 * TN + ch * 8;
+                    if (t < M) {
+                        const u32x4 vv = *reinterpret_cast<const u32x4*>(ew + r * EROW + ch * 16);
+                        if (n + 7 < NC) {
+                            *reinterpret_cast<u32x4*>(C + t * ldc + n) = vv;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (n + e < NC) C[t * ldc + n + e] = (bf16_t)((vv[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+                        }
+                    }
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < TM; ++it) {
+            const int64_t t = m0 + wm * 32 * TM + it * 32 + (lane & 31);
+            if (t >= M) continue;
+            bf16_t* crow = C + t * ldc;
+#pragma unroll
+            for (int jw = 0; jw < TN; ++jw)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int64_t n = n0 + wn * 32 * TN + jw * 32 + 8 * g + 4 * (lane >> 5);
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (n + e < NC) crow[n + e] = f32_to_bf16(acc[jw][it][4 * g + e]);
                 }
-            }
+        }
     }
 }
 
@@ -254,19 +329,30 @@ static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * 
 size_t mfma_fwd_workspace(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, BK) * 2); }
 size_t mfma_bwd_input_workspace(int64_t N, int64_t K) { return (size_t)(round_up(K, 32) * round_up(N, BK) * 2); }
 
-static hipError_t launch_gemm(const bf16_t* A, int64_t lda, const u32x4* frag, bf16_t* C, int64_t ldc, int64_t M,
-                              int64_t NC, int64_t R, int64_t R16, hipStream_t st) {
+template <int TM, int TN>
+static hipError_t launch_gemm_cfg(const bf16_t* A, int64_t lda, const u32x4* frag, bf16_t* C, int64_t ldc, int64_t M,
+                                  int64_t NC, int64_t R, int64_t R16, hipStream_t st) {
+    using Cfg = GemmCfg<TM, TN>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           2 * STAGE);
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<TM, TN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_B);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((NC + BN - 1) / BN);
-    hipLaunchKernelGGL(gemm_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 2 * STAGE, st, A, lda, frag, C,
-                       ldc, M, NC, R, R16, tiles_m, tiles_n);
+    const int tiles_m = (int)((M + Cfg::BMT - 1) / Cfg::BMT), tiles_n = (int)((NC + Cfg::BNT - 1) / Cfg::BNT);
+    hipLaunchKernelGGL((gemm_kernel<TM, TN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), Cfg::LDS_B, st, A, lda,
+                       frag, C, ldc, M, NC, R, R16, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+// Tile choice: the largest tile that still gives every compute unit (256) a workgroup.
+static hipError_t launch_gemm(const bf16_t* A, int64_t lda, const u32x4* frag, bf16_t* C, int64_t ldc, int64_t M,
+                              int64_t NC, int64_t R, int64_t R16, hipStream_t st) {
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((NC + bn - 1) / bn); };
+    if (tiles(256, 256) >= 192) return launch_gemm_cfg<4, 4>(A, lda, frag, C, ldc, M, NC, R, R16, st);
+    if (tiles(256, 128) >= 192) return launch_gemm_cfg<4, 2>(A, lda, frag, C, ldc, M, NC, R, R16, st);
+    return launch_gemm_cfg<2, 2>(A, lda, frag, C, ldc, M, NC, R, R16, st);
 }
 
 hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
