@@ -59,7 +59,7 @@ bool mfma_bwd_input_ok(int64_t T, int64_t N, int dtype) {
 
 bool mfma_bwd_alpha_ok(int64_t T, int64_t N, int64_t K, int dtype) {
     (void)K;
-    return dtype == BCQ_BF16 && T >= 64 && N % 8 == 0 && N >= 8;  // rows of dy 16-byte aligned
+    return dtype == BCQ_BF16 && T >= 64 && N % 8 == 0 && N >= 8 && K >= 8;  // rows of dy 16-byte aligned
 }
 
 size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype) {
@@ -200,7 +200,7 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
     s = check_device();
     if (s != BCQ_OK) return s;
     if (workspace && mfma_bwd_alpha_ok(T, N, K, dtype))
-        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, q_train, grad_scale, dalpha, workspace,
+        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, workspace,
                                                (hipStream_t)stream));
     return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, q, q_train, grad_scale, dalpha,
                                               (hipStream_t)stream));

@@ -55,7 +55,7 @@ hipError_t launch_bwd_input_mfma(const uint32_t* packed, const float* alpha, con
                                  int64_t K, int q, void* dx, void* workspace, hipStream_t st);
 size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q);
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q_train, float grad_scale, float* dalpha, void* workspace,
+                                 int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
                                  hipStream_t st);
 
 }  // namespace bcq

@@ -212,23 +212,12 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWB);
     };
-    auto compute = [&](int buf, int64_t next_step) {
+    auto mfma_slice = [&](int kk) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) read_x(buf, kk + 1);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), xf[kk & 1][i], acc[j][i],
-                                                                        0, 0, 0);
-            load_b(kk, next_step);
-            // issue order inside the slice: LDS reads of the next slice, the MFMAs, then the weight refill
-            if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, TM, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+            for (int i = 0; i < TM; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), xf[kk & 1][i], acc[j][i], 0, 0, 0);
     };
 
     const int64_t steps = R16 * 16 / BK;
@@ -240,15 +229,33 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     __syncthreads();
     read_x(0, 0);
 
+    // One K-step = four 16-slices.  Slices 0..2: issue the LDS reads of the next slice, the MFMAs of this one,
+    // then refill this slice's weight registers for the next K-step (a full step of latency cover).  The LDS
+    // hand-over to the next stage (write, barrier, first fragment read) sits BEFORE the MFMAs of slice 3, whose
+    // operands are already in registers, so the matrix pipe stays busy across the barrier.
     for (int64_t s = 0; s < steps; ++s) {
         const int buf = (int)(s & 1);
         const int64_t nx = s < last ? s + 1 : last;
         load_a(nx * BK);
         __builtin_amdgcn_sched_barrier(0);
-        compute(buf, nx);
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            read_x(buf, kk + 1);
+            mfma_slice(kk);
+            load_b(kk, nx);
+            __builtin_amdgcn_sched_group_barrier(0x100, TM, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         store_a(buf ^ 1);
         __syncthreads();
         read_x(buf ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(3);
+        load_b(3, nx);
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -383,19 +390,61 @@ hipError_t launch_bwd_input_mfma(const uint32_t* packed, const float* alpha, con
 // G is one dense contraction over the tokens (2 T N K matrix-core flops for ALL planes together, instead of
 // 2 q T N K for q plane products); the sign planes only enter a signed row sum of the accumulators.
 //
-// Workgroup: 256 (k) x 256 (n) tile of G^T for one slice of the tokens; 4 waves in a 2 x 2 grid, each
-// 128 x 128 = 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 with X^T as first and dY^T as second operand, so a lane
-// holds one n and 16 k of every tile.  Both operands need the token index innermost: each thread loads an
-// 8 (tokens) x 8 (columns) block with eight 16-byte loads, transposes it in registers (32 v_perm) and writes
-// eight 16-byte rows into an XOR-swizzled LDS tile [column][64 tokens]; writes and fragment reads are
-// bank-conflict free.  Partial sums per (token slice, k tile) go to the workspace; a second kernel adds them
-// in a fixed order (no floating-point atomics, bit-reproducible).
+// Both MFMA operands need the token index innermost, which neither activation has in memory.  LDS fragment
+// reads are the scarce resource of a compute unit (a 16-byte-per-lane read instruction takes ~16 clocks), so
+// only ONE operand may pass through LDS:
+//   1. transpose_frag_kernel rewrites the smaller activation (x if K <= N, else dy) into MFMA fragment order
+//      with the token index innermost (8 x 8 register transposes); its fragments are then loaded straight
+//      from global memory, 1 KiB coalesced per wave load, exactly like the expanded weights of the forward.
+//   2. dalpha_kernel: 256 (k) x 256 (n) tile of G^T for one slice of the tokens; 4 waves in a 2 x 2 grid, each
+//      128 x 128 = 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 with X^T as first and dY^T as second operand, so a
+//      lane holds one n and 16 k of every tile.  The other activation goes global -> registers -> 8 x 8
+//      transpose (32 v_perm) -> XOR-swizzled LDS tile [column][64 tokens]; writes and fragment reads are
+//      bank-conflict free.  The epilogue forms the signed sums over k for every trained plane.
+//   3. dalpha_reduce_kernel adds the partial sums of all (token slice, k tile) pairs in a fixed order (no
+//      floating-point atomics, bit-reproducible).
 constexpr int DA_TILE = 256;               // k and n extent of a workgroup tile
-constexpr int DA_STAGE = DA_TILE * 128;    // bytes per operand per LDS stage: 256 columns x 64 tokens x 2 B
+constexpr int DA_STAGE = DA_TILE * 128;    // bytes per LDS stage: 256 columns x 64 tokens x 2 B
 
 __device__ __forceinline__ int da_swz(int col, int chunk) { return col * 128 + ((chunk ^ (col & 7) ^ ((col >> 3) & 7)) << 4); }
 
-__global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ DY,
+// 8 x 8 transpose of 16-bit elements: in[r] holds row r (8 elements), out[c] holds column c.
+__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            out[c][w] = __builtin_amdgcn_perm(in[2 * w + 1][c >> 1], in[2 * w][c >> 1], (c & 1) ? 0x07060302u : 0x05040100u);
+}
+
+// act[T][C] (row-major bf16) -> fragments with the token index innermost: for column tile ct (32 columns) and
+// token slice ks (16 tokens) one 1 KiB block; lane (c % 32) + 32 g holds tokens 16 ks + 8 g .. + 7 of column c.
+// Tokens >= T (up to T16 * 16) and columns >= C are written as zeros.
+__global__ __launch_bounds__(256) void transpose_frag_kernel(const bf16_t* __restrict__ act, int64_t T, int64_t C,
+                                                             int64_t T16, u32x4* __restrict__ frag) {
+    const int cb = threadIdx.x & 15, tbl = threadIdx.x >> 4;       // 16 column blocks x 16 token blocks per group
+    const int64_t c0 = ((int64_t)blockIdx.x * 16 + cb) * 8;       // first of 8 columns
+    const int64_t tb = (int64_t)blockIdx.y * 16 + tbl;            // block of 8 tokens
+    if (tb * 8 >= T16 * 16) return;
+    u32x4 in[8], out[8];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int64_t t = tb * 8 + r;
+        in[r] = (t < T && c0 < C) ? *reinterpret_cast<const u32x4*>(act + t * C + c0) : zero;
+    }
+    transpose8x8(in, out);
+    const int64_t ct = c0 / 32, ks = tb >> 1;
+    const int g = (int)(tb & 1);
+    if (ct * 32 >= ((C + 31) / 32) * 32) return;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) frag[(ct * T16 + ks) * 64 + (c0 % 32) + c + 32 * g] = out[c];
+}
+
+template <bool XG>  // XG: x comes as fragments from global memory and dy through LDS; otherwise the reverse
+__global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict__ L /* activation through LDS */,
+                                                        int64_t ldl, int64_t lcols,
+                                                        const u32x4* __restrict__ Gfrag, int64_t T16,
                                                         const uint32_t* __restrict__ packed,
                                                         float* __restrict__ part, int64_t T, int64_t N, int64_t K,
                                                         int q_train, int tiles_k, int tiles_n, int64_t tokens_per_split) {
@@ -405,9 +454,10 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
     const int tile_k = blockIdx.x % tiles_k, tile_n = blockIdx.x / tiles_k;
     const int split = blockIdx.y;
     const int64_t k0 = (int64_t)tile_k * DA_TILE, n0 = (int64_t)tile_n * DA_TILE;
-    const int64_t t_begin = (int64_t)split * tokens_per_split;
+    const int64_t t_begin = (int64_t)split * tokens_per_split;  // a multiple of 64
     const int64_t t_end = (t_begin + tokens_per_split < T) ? t_begin + tokens_per_split : T;
     const int64_t steps = (t_end - t_begin + 63) / 64;
+    const int64_t step0 = t_begin / 64;
 
     f32x16 acc[4][4];  // [k tile][n tile]
 #pragma unroll
@@ -417,97 +467,125 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // global -> register blocks: thread = (cb = column block of 8, tb = token block of 8)
+    // LDS-side activation: thread = (cb = column block of 8, tb = token block of 8)
     const int cb = tid & 31, tb = tid >> 5;
-    int64_t xcol = k0 + cb * 8, dcol = n0 + cb * 8;
-    xcol = xcol < K - 8 ? xcol : K - 8;  // clamped columns only feed outputs that are never stored
-    dcol = dcol < N - 8 ? dcol : N - 8;
-    u32x4 xr[8], dr[8];
+    int64_t lcol = (XG ? n0 : k0) + cb * 8;
+    lcol = lcol < lcols - 8 ? lcol : lcols - 8;  // clamped columns only feed outputs that are never stored
+    u32x4 lr[8];
     auto load_blocks = [&](int64_t step) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const int64_t t = t_begin + step * 64 + tb * 8 + r;
-            const int64_t tc = t < T ? t : T - 1;
-            u32x4 xv = *reinterpret_cast<const u32x4*>(X + tc * K + xcol);
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            xr[r] = t < t_end ? xv : zero;  // tokens outside the slice contribute nothing
-            dr[r] = *reinterpret_cast<const u32x4*>(DY + tc * N + dcol);
+            int64_t t = (step0 + step) * 64 + tb * 8 + r;
+            t = t < T ? t : T - 1;  // such rows meet zero fragments of the other operand
+            lr[r] = *reinterpret_cast<const u32x4*>(L + t * ldl + lcol);
         }
     };
-    // 8 x 8 transpose of 16-bit elements, then 8 row writes of 16 B
     auto store_blocks = [&](int buf) {
-        unsigned char* sx = smem + buf * 2 * DA_STAGE;
-        unsigned char* sd = sx + DA_STAGE;
+        unsigned char* sl = smem + buf * DA_STAGE;
+        u32x4 o[8];
+        transpose8x8(lr, o);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            u32x4 ox, od;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-                ox[w] = __builtin_amdgcn_perm(xr[2 * w + 1][c >> 1], xr[2 * w][c >> 1], sel);
-                od[w] = __builtin_amdgcn_perm(dr[2 * w + 1][c >> 1], dr[2 * w][c >> 1], sel);
-            }
-            *reinterpret_cast<u32x4*>(sx + da_swz(cb * 8 + c, tb)) = ox;
-            *reinterpret_cast<u32x4*>(sd + da_swz(cb * 8 + c, tb)) = od;
-        }
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(sl + da_swz(cb * 8 + c, tb)) = o[c];
     };
-    bf16x8 xf[2][4], df[2][4];
+    bf16x8 lf[2][4];
+    const int lbase = (XG ? wn : wm) * 128 + (lane & 31);
     auto read_frags = [&](int buf, int kk) {
-        const unsigned char* sx = smem + buf * 2 * DA_STAGE;
-        const unsigned char* sd = sx + DA_STAGE;
+        const unsigned char* sl = smem + buf * DA_STAGE;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sx + da_swz(wm * 128 + i * 32 + (lane & 31), kk * 2 + (lane >> 5)));
-            df[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sd + da_swz(wn * 128 + i * 32 + (lane & 31), kk * 2 + (lane >> 5)));
-        }
+        for (int i = 0; i < 4; ++i)
+            lf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sl + da_swz(lbase + i * 32, kk * 2 + (lane >> 5)));
+    };
+    // global-side fragments of this wave: 4 column tiles
+    const int64_t gct_count = ((XG ? K : N) + 31) / 32;
+    const int64_t gct0 = ((XG ? k0 + wm * 128 : n0 + wn * 128)) / 32;
+    const u32x4* gptr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int64_t ct = gct0 + j;
+        ct = ct < gct_count ? ct : gct_count - 1;
+        gptr[j] = Gfrag + (ct * T16 + step0 * 4) * 64 + lane;
+    }
+    u32x4 g[4][4];  // [kk][tile]
+    auto load_g = [&](int kk, int64_t step) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) g[kk][j] = gptr[j][(step * 4 + kk) * 64];
+    };
+    auto mfma_slice = [&](int kk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (XG)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(g[kk][i]), lf[kk & 1][j], acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[kk & 1][i], as_bf16x8(g[kk][j]), acc[i][j], 0, 0, 0);
+            }
     };
 
+    const int64_t last = steps - 1;
     load_blocks(0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) load_g(kk, 0);
     store_blocks(0);
     __syncthreads();
     read_frags(0, 0);
     for (int64_t s = 0; s < steps; ++s) {
         const int buf = (int)(s & 1);
-        const int64_t nx = s + 1 < steps ? s + 1 : s;
+        const int64_t nx = s < last ? s + 1 : last;
         load_blocks(nx);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) read_frags(buf, kk + 1);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[kk & 1][i], df[kk & 1][j], acc[i][j], 0, 0, 0);
-            if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        for (int kk = 0; kk < 3; ++kk) {
+            read_frags(buf, kk + 1);
+            mfma_slice(kk);
+            load_g(kk, nx);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (s + 1 < steps) store_blocks(buf ^ 1);
+        store_blocks(buf ^ 1);
         __syncthreads();
-        if (s + 1 < steps) read_frags(buf ^ 1, 0);
+        read_frags(buf ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(3);
+        load_g(3, nx);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
+    __syncthreads();
 
+#ifdef BCQ_PROBE_NO_EPI
+    if (acc[0][0][0] != 123.456f) return;
+#endif
     // epilogue: signed sums over this wave's 128 k for each plane; lane owns n = n_base + j*32 + lane%32
-    float* red = reinterpret_cast<float*>(smem);  // [plane][wm][256 n]; the loop above ended with a barrier
+    float* red = reinterpret_cast<float*>(smem);  // [plane][wm][256 n]
     const int64_t Kw = K / 32;
     for (int p = 0; p < q_train; ++p) {
+        uint32_t words[4][4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t n = n0 + wn * 128 + j * 32 + (lane & 31);
             const int64_t nc = n < N ? n : N - 1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int64_t kt = (k0 + wm * 128 + i * 32) / 32;
+                kt = kt < Kw ? kt : Kw - 1;  // tiles beyond K hold zero accumulators (zero or unused fragments)
+                words[i][j] = packed[((int64_t)p * N + nc) * Kw + kt] >> (4 * (lane >> 5));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int64_t kt = (k0 + wm * 128 + i * 32) / 32;
-                if (kt < Kw) {
-                    const uint32_t word = packed[((int64_t)p * N + nc) * Kw + kt] >> (4 * (lane >> 5));
+                const bool live = (k0 + wm * 128 + i * 32) < K;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int bit = 8 * (v >> 2) + (v & 3);
-                        s += ((word >> bit) & 1u) ? acc[i][j][v] : -acc[i][j][v];
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int bit = 8 * (v >> 2) + (v & 3);
+                    const float a = live ? acc[i][j][v] : 0.f;
+                    s += ((words[i][j] >> bit) & 1u) ? a : -a;
                 }
             }
             s += __shfl_xor(s, 32);
@@ -527,50 +605,85 @@ __global__ __launch_bounds__(256) void dalpha_reduce_kernel(const float* __restr
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= count) return;
     float s = 0.f;
-    for (int p = 0; p < parts; ++p) s += part[(int64_t)p * count + idx];
+    int p = 0;
+    for (; p + 8 <= parts; p += 8) {  // eight independent loads in flight, added in index order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(p + u) * count + idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; p < parts; ++p) s += part[(int64_t)p * count + idx];
     dalpha[idx] = scale * s;
 }
 
-static void dalpha_plan(int64_t T, int64_t N, int64_t K, int* tiles_k, int* tiles_n, int* splits, int64_t* per_split) {
-    *tiles_k = (int)((K + DA_TILE - 1) / DA_TILE);
-    *tiles_n = (int)((N + DA_TILE - 1) / DA_TILE);
-    const int64_t tiles = (int64_t)*tiles_k * *tiles_n;
-    int64_t s = (512 + tiles - 1) / tiles;            // aim at two workgroups per compute unit
+struct DalphaPlan {
+    int tiles_k, tiles_n, splits;
+    int64_t per_split, T16;
+    bool xg;
+    size_t frag_bytes, part_bytes;
+};
+
+static DalphaPlan dalpha_plan(int64_t T, int64_t N, int64_t K, int q) {
+    DalphaPlan pl;
+    pl.tiles_k = (int)((K + DA_TILE - 1) / DA_TILE);
+    pl.tiles_n = (int)((N + DA_TILE - 1) / DA_TILE);
+    const int64_t tiles = (int64_t)pl.tiles_k * pl.tiles_n;
+    int64_t s = (256 + tiles - 1) / tiles;            // one workgroup per compute unit
     const int64_t max_s = (T + 255) / 256;            // at least 256 tokens (4 steps) per slice
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
-    int64_t per = ((T + s - 1) / s + 63) / 64 * 64;
-    *per_split = per;
-    *splits = (int)((T + per - 1) / per);
+    pl.per_split = ((T + s - 1) / s + 63) / 64 * 64;
+    pl.splits = (int)((T + pl.per_split - 1) / pl.per_split);
+    pl.T16 = (T + 63) / 64 * 4;
+    pl.xg = (K <= N);
+    const int64_t gcols = pl.xg ? K : N;
+    pl.frag_bytes = (size_t)(((gcols + 31) / 32) * pl.T16 * 1024);
+    pl.part_bytes = (size_t)pl.splits * pl.tiles_k * q * N * sizeof(float);
+    return pl;
 }
 
 size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q) {
-    int tk, tn, sp;
-    int64_t per;
-    dalpha_plan(T, N, K, &tk, &tn, &sp, &per);
-    return (size_t)sp * tk * q * N * sizeof(float);
+    const DalphaPlan pl = dalpha_plan(T, N, K, q);
+    return pl.frag_bytes + pl.part_bytes;
 }
 
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q_train, float grad_scale, float* dalpha, void* workspace,
+                                 int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
                                  hipStream_t st) {
     static bool attr_set = false;
-    const int lds = 4 * DA_STAGE;
+    const int lds = 2 * DA_STAGE;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)dalpha_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipError_t e = hipFuncSetAttribute((const void*)dalpha_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)dalpha_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int tk, tn, sp;
-    int64_t per;
-    dalpha_plan(T, N, K, &tk, &tn, &sp, &per);
-    hipLaunchKernelGGL(dalpha_kernel, dim3((unsigned)(tk * tn), (unsigned)sp), dim3(256), lds, st, (const bf16_t*)x,
-                       (const bf16_t*)dy, packed, (float*)workspace, T, N, K, q_train, tk, tn, per);
+    const DalphaPlan pl = dalpha_plan(T, N, K, q);
+    u32x4* frag = reinterpret_cast<u32x4*>(workspace);
+    float* part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.frag_bytes);
+    const bf16_t* gact = (const bf16_t*)(pl.xg ? x : dy);
+    const bf16_t* lact = (const bf16_t*)(pl.xg ? dy : x);
+    const int64_t gcols = pl.xg ? K : N, lcols = pl.xg ? N : K;
+    {
+        dim3 grid((unsigned)((gcols + 127) / 128), (unsigned)((pl.T16 * 2 + 15) / 16));
+        hipLaunchKernelGGL(transpose_frag_kernel, grid, dim3(256), 0, st, gact, T, gcols, pl.T16, frag);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)(pl.tiles_k * pl.tiles_n), (unsigned)pl.splits);
+    if (pl.xg)
+        hipLaunchKernelGGL(dalpha_kernel<true>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
+                           T, N, K, q_train, pl.tiles_k, pl.tiles_n, pl.per_split);
+    else
+        hipLaunchKernelGGL(dalpha_kernel<false>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
+                           T, N, K, q_train, pl.tiles_k, pl.tiles_n, pl.per_split);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)q_train * N;
     hipLaunchKernelGGL(dalpha_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
-                       (const float*)workspace, dalpha, count, sp * tk, grad_scale);
+                       (const float*)part, dalpha, count, pl.splits * pl.tiles_k, grad_scale);
     return hipGetLastError();
 }
 
