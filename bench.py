@@ -160,18 +160,24 @@ def main():
         from oracle import bcq_oracle as oracle
         kind = "out"
         N, K = synth.layer_shape(h, kind)
-        Ts = min(T, 128)
         W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
         a_ref, planes_ref = oracle.quantize(W, q)
-        xs = synth.activations(args.config, kind, T, K, 1, dtype)[:Ts]
-        dys = synth.activations(args.config, kind, T, N, 2, dtype)[:Ts]
-        c0 = time.perf_counter()
-        oracle.fwd(a_ref, planes_ref, xs)
-        oracle.bwd_input(a_ref, planes_ref, dys)
-        oracle.bwd_alpha(planes_ref, xs, dys)
-        c1 = time.perf_counter()
-        cpu = {"value": round(6.0 * Ts * N * K / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "seconds": round(c1 - c0, 2),
+        x_all = synth.activations(args.config, kind, T, K, 1, dtype)
+        dy_all = synth.activations(args.config, kind, T, N, 2, dtype)
+
+        def oracle_pass(ts):
+            c0 = time.perf_counter()
+            oracle.fwd(a_ref, planes_ref, x_all[:ts])
+            oracle.bwd_input(a_ref, planes_ref, dy_all[:ts])
+            oracle.bwd_alpha(planes_ref, x_all[:ts], dy_all[:ts])
+            return time.perf_counter() - c0
+
+        probe_t = min(T, 64)
+        probe_s = oracle_pass(probe_t)                       # sizes the sample: aim at about 15 s of CPU work
+        Ts = int(max(probe_t, min(T, probe_t * 15.0 / max(probe_s, 1e-3))))
+        secs = oracle_pass(Ts)
+        cpu = {"value": round(6.0 * Ts * N * K / secs / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(secs, 2),
                "sample": "fwd+dx+dalpha of the %dx%d '%s' layer, q=%d, first %d of %d tokens, fp64 naive loops"
                          % (N, K, kind, q, Ts, T)}
 

@@ -1,0 +1,118 @@
+"""Parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py times
+(workspace from bcq_workspace_bytes, transposed twin given).  The oracle cannot sweep these sizes in seconds,
+so outputs are compared on seeded samples it computes one by one: >= 4096 random entries plus 8 complete rows
+and 8 complete columns per output tensor, and 64 complete rows of dalpha over all tokens.  The quantizer is
+compared in full (bit-exact planes and alpha)."""
+import numpy as np
+import pytest
+
+from _util import nmax_err, packed_to_dev, packed_to_host, to_dev, to_host, tol_for
+from paper_2210_03858_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bcq():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2210_03858_amd as p
+    p.load()
+    return p
+
+
+def _ws(bcq, op, T, N, K, q, code):
+    import torch
+    nbytes = bcq.workspace_bytes(op, T, N, K, q, code)
+    return torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
+
+
+def _quantize_and_check(bcq, oracle, W, q):
+    import torch
+    a_ref, b_ref, margin = oracle.quantize(W, q, with_margin=True)
+    alpha, packed, _ = bcq.bcq_quantize(to_dev(W), q)
+    torch.cuda.synchronize()
+    ok = ~(margin < 2.0 ** -40).any(axis=0)
+    assert (~ok).sum() <= max(1, W.shape[0] // 1000)
+    assert np.array_equal(alpha.cpu().numpy()[:, ok].view(np.uint32), a_ref[:, ok].view(np.uint32))
+    assert np.array_equal(packed_to_host(packed)[:, ok], oracle.pack(b_ref)[:, ok])
+    return a_ref, b_ref, alpha, packed
+
+
+def _sampled_layer(bcq, oracle, config, kind, T, q, dtype, outliers=False, full=False, seed=0, q_train=None):
+    import torch
+    h = synth.CONFIGS[config]["h"]
+    N, K = synth.layer_shape(h, kind)
+    W = synth.weights(config, kind, N, K, outliers=outliers)
+    a_ref, b_ref, alpha, packed = _quantize_and_check(bcq, oracle, W, q)
+    x = synth.activations(config, kind, T, K, 1, dtype)
+    dy = synth.activations(config, kind, T, N, 2, dtype)
+    d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
+    code = 0 if dtype == "f32" else 1
+    twin = bcq.bcq_pack_transposed(packed)
+    y = bcq.bcq_linear_fwd(packed, alpha, d_x, workspace=_ws(bcq, 1, T, N, K, q, code))
+    dx = bcq.bcq_linear_bwd_input(packed, alpha, d_dy, packed_t=twin, workspace=_ws(bcq, 2, T, N, K, q, code))
+    da = bcq.bcq_linear_bwd_alpha(packed, d_x, d_dy, q_train=q_train, workspace=_ws(bcq, 3, T, N, K, q, code))
+    torch.cuda.synchronize()
+    y, dx, da = to_host(y), to_host(dx), to_host(da)
+    tol = tol_for(dtype)
+    if full:
+        ref_y, ref_dx = oracle.fwd(a_ref, b_ref, x), oracle.bwd_input(a_ref, b_ref, dy)
+        ref_da = oracle.bwd_alpha(b_ref, x, dy, q_train=q_train)
+        errs = (nmax_err(y, ref_y), nmax_err(dx, ref_dx), nmax_err(da, ref_da))
+    else:
+        tt, nn = synth.sample_indices(1000 + seed, T, N, 4096)
+        ref = oracle.fwd_at(a_ref, b_ref, x, tt, nn)
+        e_y = nmax_err(y[tt, nn], ref)
+        tt, kk = synth.sample_indices(2000 + seed, T, K, 4096)
+        ref = oracle.bwd_input_at(a_ref, b_ref, dy, tt, kk)
+        e_dx = nmax_err(dx[tt, kk], ref)
+        rows = np.random.default_rng(3000 + seed).choice(N, size=min(64, N), replace=False)
+        ref = oracle.bwd_alpha_rows(b_ref, x, dy, rows, q_train=q_train)
+        e_da = nmax_err(da[:, rows], ref)
+        errs = (e_y, e_dx, e_da)
+    assert errs[0] <= tol, ("fwd", errs)
+    assert errs[1] <= tol, ("bwd_input", errs)
+    assert errs[2] <= tol, ("bwd_alpha", errs)
+    return errs
+
+
+@pytest.mark.parametrize("kind", synth.LAYER_KINDS)
+def test_config2_gpt2_medium_block(bcq, oracle, kind):
+    """d = 1024, q = 4, bf16, T = 8 x 512: the workload bench.py times."""
+    _sampled_layer(bcq, oracle, 2, kind, 4096, 4, "bf16", seed=synth.LAYER_KINDS.index(kind))
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4])
+@pytest.mark.parametrize("T", [1, 4, 8])
+def test_config3_decode_regime(bcq, oracle, q, T):
+    """d = 1280 layers at 1, 4 and 8 tokens, compared in full."""
+    for kind in ("qkv", "mlp_down"):
+        _sampled_layer(bcq, oracle, 3, kind, T, q, "bf16", full=True)
+
+
+@pytest.mark.parametrize("q,kind", [(1, "out"), (2, "mlp_down"), (3, "mlp_up"), (4, "qkv")])
+def test_config3_training_regime(bcq, oracle, q, kind):
+    _sampled_layer(bcq, oracle, 3, kind, 4 * 1024, q, "bf16", seed=10 + q)
+
+
+@pytest.mark.parametrize("kind", ["out", "mlp_up", "mlp_down"])
+def test_config4_opt13b_outlier_rows(bcq, oracle, kind):
+    """d = 2048, q = 3, T = 8 x 2048, 0.1 % of the rows scaled by 10 before quantization."""
+    _sampled_layer(bcq, oracle, 4, kind, 8 * 2048, 3, "bf16", outliers=True, seed=20)
+
+
+@pytest.mark.parametrize("T", [1, 16, 256, 4096])
+def test_config5_token_sweep(bcq, oracle, T):
+    """d = 2560, q = 4: tokens 1, 16, 256, 4096 cross from the streaming kernels to the matrix-core kernels."""
+    kind = {1: "mlp_up", 16: "qkv", 256: "mlp_down", 4096: "mlp_up"}[T]
+    _sampled_layer(bcq, oracle, 5, kind, T, 4, "bf16", seed=30 + T, q_train=1 if T == 256 else None)
+
+
+def test_config5_quantizer_all_kinds(bcq, oracle):
+    """Greedy quantizer on every layer shape of the d = 2560 stack, two seeded layers each, in full."""
+    for layer in range(2):
+        for kind in synth.LAYER_KINDS:
+            N, K = synth.layer_shape(2560, kind)
+            W = synth.weights(5, kind, N, K, extra=layer)
+            _quantize_and_check(bcq, oracle, W, 4)
