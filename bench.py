@@ -146,7 +146,9 @@ def main():
         dom = max(per_op, key=lambda k: per_op[k]["ms"])
         d = per_op[dom]
         achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "bcq_linear_" + dom, "achieved": round(achieved, 3),
+        main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
+                       "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
+        roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
                     "traffic": None, "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
                     "launches": d["launches"],
@@ -158,28 +160,26 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import bcq_oracle as oracle
-        kind = "out"
-        N, K = synth.layer_shape(h, kind)
-        W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
-        a_ref, planes_ref = oracle.quantize(W, q)
-        x_all = synth.activations(args.config, kind, T, K, 1, dtype)
-        dy_all = synth.activations(args.config, kind, T, N, 2, dtype)
-
-        def oracle_pass(ts):
+        budget_s, spent, flops_done, done = 12.0, 0.0, 0.0, []
+        for kind in sorted(kinds, key=lambda k: synth.layer_shape(h, k)[0] * synth.layer_shape(h, k)[1]):
+            if spent > budget_s:
+                break
+            N, K = synth.layer_shape(h, kind)
+            W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
+            a_ref, planes_ref = oracle.quantize(W, q)
+            Ts = min(T, 4096)
+            xs = synth.activations(args.config, kind, T, K, 1, dtype)[:Ts]
+            dys = synth.activations(args.config, kind, T, N, 2, dtype)[:Ts]
             c0 = time.perf_counter()
-            oracle.fwd(a_ref, planes_ref, x_all[:ts])
-            oracle.bwd_input(a_ref, planes_ref, dy_all[:ts])
-            oracle.bwd_alpha(planes_ref, x_all[:ts], dy_all[:ts])
-            return time.perf_counter() - c0
-
-        probe_t = min(T, 64)
-        probe_s = oracle_pass(probe_t)                       # sizes the sample: aim at about 15 s of CPU work
-        Ts = int(max(probe_t, min(T, probe_t * 15.0 / max(probe_s, 1e-3))))
-        secs = oracle_pass(Ts)
-        cpu = {"value": round(6.0 * Ts * N * K / secs / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "seconds": round(secs, 2),
-               "sample": "fwd+dx+dalpha of the %dx%d '%s' layer, q=%d, first %d of %d tokens, fp64 naive loops"
-                         % (N, K, kind, q, Ts, T)}
+            oracle.fwd(a_ref, planes_ref, xs)
+            oracle.bwd_input(a_ref, planes_ref, dys)
+            oracle.bwd_alpha(planes_ref, xs, dys)
+            spent += time.perf_counter() - c0
+            flops_done += 6.0 * Ts * N * K
+            done.append("%s %dx%d x %d tokens" % (kind, N, K, Ts))
+        cpu = {"value": round(flops_done / spent / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(spent, 2),
+               "sample": "fwd+dx+dalpha, q=%d, fp64 naive loops, layers: %s" % (q, "; ".join(done))}
 
     out = {
         "metric": "BCQ linear fwd+bwd effective TFLOP/s",
