@@ -52,6 +52,11 @@ bcq_status check_workspace(const void* ws, size_t have, size_t need) {
 // Token count from which the tiled matrix-core kernels are used (bf16 activations, workspace given).
 constexpr int64_t kMfmaMinTokens = 32;
 
+// Small-token kernels: bf16, fewer tokens than the tiled kernels want.
+bool small_fwd_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T < kMfmaMinTokens; }
+bool small_bwd_alpha_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T <= 16; }
+bool small_bwd_input_ok(int64_t T, int64_t N, int dtype) { return dtype == BCQ_BF16 && T < kMfmaMinTokens && N % 32 == 0; }
+
 bool mfma_fwd_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T >= kMfmaMinTokens; }
 bool mfma_bwd_input_ok(int64_t T, int64_t N, int dtype) {
     return dtype == BCQ_BF16 && T >= kMfmaMinTokens && N % 8 == 0;  // rows of dy must be 16-byte aligned
@@ -67,7 +72,9 @@ size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype)
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
         case BCQ_OP_FWD: return mfma_fwd_ok(T, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
-        case BCQ_OP_BWD_INPUT: return mfma_bwd_input_ok(T, N, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
+        case BCQ_OP_BWD_INPUT:
+            if (small_bwd_input_ok(T, N, dtype)) return bcq::small_bwd_input_workspace(T, N, q);
+            return mfma_bwd_input_ok(T, N, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
         case BCQ_OP_BWD_ALPHA: return mfma_bwd_alpha_ok(T, N, K, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, q) : 0;
         default: return 0;
     }
@@ -162,6 +169,7 @@ bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (small_fwd_ok(T, dtype)) return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, (hipStream_t)stream));
     if (workspace && mfma_fwd_ok(T, dtype))
         return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, q, y, workspace, (hipStream_t)stream));
     return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, q, y, (hipStream_t)stream));
@@ -181,6 +189,8 @@ bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (workspace && packed_t && small_bwd_input_ok(T, N, dtype))
+        return done(bcq::launch_bwd_input_small(packed_t, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
     if (workspace && mfma_bwd_input_ok(T, N, dtype))
         return done(bcq::launch_bwd_input_mfma(packed, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
     return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, q, dx, (hipStream_t)stream));
@@ -199,6 +209,9 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
+    if (small_bwd_alpha_ok(T, dtype))
+        return done(bcq::launch_bwd_alpha_small(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha,
+                                                (hipStream_t)stream));
     if (workspace && mfma_bwd_alpha_ok(T, N, K, dtype))
         return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, workspace,
                                                (hipStream_t)stream));
