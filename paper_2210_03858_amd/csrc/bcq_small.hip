@@ -10,9 +10,9 @@
 //
 // Work split: a workgroup owns 16 R rows of the plane matrix and all tokens of one 16-token tile; its W waves
 // split the contraction range and add their partial 16 x 16 tiles through LDS in a fixed order (deterministic).
-// Each lane reads its own 8 bytes of every plane row per 256-column segment, so a plane word is fetched by
-// exactly one lane of one wave.  The contraction index is permuted inside the MFMA (lane group g owns columns
-// 64 g .. 64 g + 63 of the segment, and a register pair holds columns c and c + 16 of a word) - legal because
+// Each lane reads its own 16 bytes of every plane row per 512-column segment (four lanes cover 64 contiguous
+// bytes of a row), so a plane word is fetched by exactly one lane of one wave.  The contraction index is permuted inside the MFMA (lane group g owns columns
+// 128 g .. 128 g + 127 of a 512-column segment, and a register pair holds columns c and c + 16 of a word) - legal because
 // both operands use the same permutation - which is what makes the one-shift expansion possible.
 //
 // The input gradient uses the transposed twin (rows = columns k of W, bits along n) and activations
@@ -62,8 +62,8 @@ __device__ __forceinline__ s_bf16x8 load_act_frag(const bf16_t* p32, int u, bool
 
 // planes: [q][rows][cw] words (canonical for FWD / DALPHA, twin for DX).  act: FWD, DALPHA: x[T][C];
 // DX: scaled activations [q][T][C].  rows x C is the plane matrix seen by this kernel (C = 32 cw).
-template <int MODE, int R>
-__global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32_t* __restrict__ planes, const bf16_t* __restrict__ act,
+template <int MODE, int R, int QP>
+__global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__ planes, const bf16_t* __restrict__ act,
                                                      const float* __restrict__ alpha, const bf16_t* __restrict__ dy,
                                                      void* __restrict__ out, int64_t T, int64_t rows, int64_t cw,
                                                      int q, int q_used, float scale, int segs_per_wave) {
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32
     const int64_t C = cw * 32;
     const bool tok_live = (t0 + rl) < T;
     const int64_t tok = tok_live ? t0 + rl : T - 1;
-    constexpr int NACC = (MODE == SMALL_DX) ? 1 : 8;
+    constexpr int NACC = (MODE == SMALL_DX) ? 1 : QP;  // planes beyond q_used read plane q_used-1 again and are dropped
 
     s_f32x4 acc[R][NACC];
 #pragma unroll
@@ -93,46 +93,108 @@ __global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32
     }
     const int64_t plane_stride = rows * cw;
 
+    // epilogue operands, requested before the main loop so that their latency is covered by it
+    float ep[R][QP][4];  // FWD: alpha_i of this lane's 4 rows; DALPHA: dy of this lane's token and 4 rows (plane 0 slot)
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            int64_t n = row0 + 16 * r + 4 * g + v;
+            const bool n_live = n < rows;
+            n = n_live ? n : rows - 1;
+            if (MODE == SMALL_FWD) {
+#pragma unroll
+                for (int i = 0; i < QP; ++i) ep[r][i][v] = (i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+            } else if (MODE == SMALL_DALPHA) {
+                ep[r][0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
+            }
+        }
+
+    // raw halves of an activation fragment (see load_act_frag), loaded early and permuted at use
+    struct ActRaw { s_u32x2 lo, hi; };
+    auto load_act_raw = [&](const bf16_t* p32, int u, bool live) {
+        ActRaw a;
+        a.lo = s_u32x2{0u, 0u};
+        a.hi = s_u32x2{0u, 0u};
+        if (live) {
+            a.lo = *reinterpret_cast<const s_u32x2*>(p32 + 4 * u);
+            a.hi = *reinterpret_cast<const s_u32x2*>(p32 + 16 + 4 * u);
+        }
+        return a;
+    };
+    auto act_frag = [&](const ActRaw& a) {
+        s_u32x4 r;
+        r[0] = __builtin_amdgcn_perm(a.hi[0], a.lo[0], 0x05040100u);
+        r[1] = __builtin_amdgcn_perm(a.hi[0], a.lo[0], 0x07060302u);
+        r[2] = __builtin_amdgcn_perm(a.hi[1], a.lo[1], 0x05040100u);
+        r[3] = __builtin_amdgcn_perm(a.hi[1], a.lo[1], 0x07060302u);
+        return __builtin_bit_cast(s_bf16x8, r);
+    };
+
     const int seg_begin = wave * segs_per_wave;
-    for (int s = 0; s < segs_per_wave; ++s) {
-        const int64_t w0 = ((int64_t)(seg_begin + s) * 8) + 2 * g;  // first of this lane's two words
-        if ((int64_t)(seg_begin + s) * 8 >= cw) break;               // whole wave leaves together
-        const bool w_live0 = w0 < cw, w_live1 = (w0 + 1) < cw;
-        const int64_t wc0 = w_live0 ? w0 : cw - 1, wc1 = w_live1 ? w0 + 1 : cw - 1;
-        uint32_t bits[R][8][2];
+    const int npass = (MODE == SMALL_DX) ? q_used : 1;
+    constexpr int PPP = (MODE == SMALL_DX) ? 1 : QP;          // planes per pass; DX: one pass per plane
+    for (int pass = 0; pass < npass; ++pass) {
+        const bf16_t* act_row = act + ((int64_t)pass * T + tok) * C;  // pass = plane for DX, 0 otherwise
+        const uint32_t* pbase = planes + (int64_t)pass * ((MODE == SMALL_DX) ? plane_stride : 0);
+        for (int s = 0; s < segs_per_wave; ++s) {
+            if ((int64_t)(seg_begin + s) * 16 >= cw) break;                // whole wave leaves together
+            const int64_t w0 = ((int64_t)(seg_begin + s) * 16) + 4 * g;  // first of this lane's four words
+            // one 16-byte load per plane row when the four words exist (cw % 4 == 0 keeps it aligned)
+            const bool quad = (w0 + 3 < cw) && ((cw & 3) == 0);
+            int64_t wc[4];
+            bool wl[4];
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+            for (int j = 0; j < 4; ++j) {
+                wl[j] = (w0 + j) < cw;
+                wc[j] = wl[j] ? w0 + j : cw - 1;
+            }
+            uint32_t bits[R][PPP][4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i < q_used) {
-                    bits[r][i][0] = prow[r][(int64_t)i * plane_stride + wc0];
-                    bits[r][i][1] = prow[r][(int64_t)i * plane_stride + wc1];
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < PPP; ++i) {
+                    const int ic = (MODE == SMALL_DX || i < q_used) ? i : q_used - 1;
+                    const uint32_t* pr = pbase + (prow[r] - planes) + (int64_t)ic * plane_stride;
+                    if (quad) {
+                        const s_u32x4 v4 = *reinterpret_cast<const s_u32x4*>(pr + w0);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bits[r][i][j] = v4[j];
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) bits[r][i][j] = pr[wc[j]];
+                    }
                 }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const bool live = tok_live && (j == 0 ? w_live0 : w_live1);
-            const int64_t col = (j == 0 ? wc0 : wc1) * 32;
-#pragma unroll 1
-            for (int u = 0; u < 4; ++u) {
-                if (MODE == SMALL_DX) {
+            for (int half = 0; half < 2; ++half) {
+                ActRaw araw[2][4];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        if (i < q_used) {
-                            const s_bf16x8 v = load_act_frag(act + ((int64_t)i * T + tok) * C + col, u, live);
+                for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-                            for (int r = 0; r < R; ++r)
-                                acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(expand_signs(bits[r][i][j], u), v,
-                                                                                    acc[r][0], 0, 0, 0);
-                        }
-                } else {
-                    const s_bf16x8 v = load_act_frag(act + tok * C + col, u, live);
+                    for (int u = 0; u < 4; ++u)
+                        araw[jj][u] = load_act_raw(act_row + wc[2 * half + jj] * 32, u, tok_live && wl[2 * half + jj]);
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = 2 * half + jj;
 #pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            if (i < q_used)
+                    for (int u = 0; u < 4; ++u) {
+                        const s_bf16x8 v = act_frag(araw[jj][u]);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int i = 0; i < PPP; ++i) {
+#if defined(BCQ_PROBE_NO_MFMA)
+                                acc[r][i][0] += __builtin_bit_cast(float, bits[r][i][j]) + (float)v[0];
+#elif defined(BCQ_PROBE_NO_EXPAND)
+                                acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, v, acc[r][i], 0, 0, 0);
+                                acc[r][i][0] += __builtin_bit_cast(float, bits[r][i][j]);
+#else
                                 acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(expand_signs(bits[r][i][j], u), v,
                                                                                     acc[r][i], 0, 0, 0);
+#endif
+                            }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
         }
@@ -140,7 +202,7 @@ __global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32
 
     // Accumulator register v of lane l: plane-matrix row 4 * (l / 16) + v of the tile, token l % 16.
     // FWD folds alpha into one tile per row block before the cross-wave sum; DALPHA keeps the planes apart.
-    constexpr int NOUT = (MODE == SMALL_DALPHA) ? 8 : 1;
+    constexpr int NOUT = (MODE == SMALL_DALPHA) ? QP : 1;
     const int nout = (MODE == SMALL_DALPHA) ? q_used : 1;
     s_f32x4 part[R][NOUT];
 #pragma unroll
@@ -148,21 +210,15 @@ __global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32
         if (MODE == SMALL_FWD) {
             s_f32x4 y = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i < q_used) {
+            for (int i = 0; i < QP; ++i)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        int64_t n = row0 + 16 * r + 4 * g + v;
-                        n = n < rows ? n : rows - 1;
-                        y[v] += alpha[(int64_t)i * rows + n] * acc[r][i][v];
-                    }
-                }
+                for (int v = 0; v < 4; ++v) y[v] += ep[r][i][v] * acc[r][i][v];  // alpha of unused planes is 0
             part[r][0] = y;
         } else if (MODE == SMALL_DX) {
             part[r][0] = acc[r][0];
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) part[r][i < NOUT ? i : 0] = acc[r][i < NACC ? i : 0];
+            for (int i = 0; i < NOUT; ++i) part[r][i] = acc[r][i < NACC ? i : 0];
         }
     }
     // cross-wave sum in wave order: red[w][r][o][lane][4]
@@ -191,7 +247,7 @@ __global__ __launch_bounds__(R == 2 ? 256 : 1024) void small_kernel(const uint32
         if (MODE == SMALL_DALPHA) {
             float d[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) d[v] = (tok_live && n + v < rows) ? bf16_to_f32(dy[tok * rows + n + v]) : 0.f;
+            for (int v = 0; v < 4; ++v) d[v] = ep[r][0][v];
 #pragma unroll
             for (int o = 0; o < NOUT; ++o)
                 if (o < nout) {
@@ -246,17 +302,30 @@ struct SmallPlan {
 
 static SmallPlan small_plan(int64_t rows, int64_t cw) {
     SmallPlan p;
-    const int64_t segs = (cw + 7) / 8;
-    // enough waves for the 1024 SIMDs of the chip: prefer two row tiles per wave, split the contraction more
-    // (up to 16 waves per workgroup) when the matrix has few rows
-    p.R = (rows / 32) * 4 >= 2048 ? 2 : 1;
+    const int64_t segs = (cw + 15) / 16;  // 512-column segments
+    // two row tiles per wave (half the activation traffic per plane byte) only when there are rows to spare
+    p.R = rows >= 16384 ? 2 : 1;
     const int64_t blocks = (rows + 16 * p.R - 1) / (16 * p.R);
-    int W = 4;
-    while (W < 16 && blocks * W < 2048 && segs >= 2 * W) W *= 2;
-    if (W > segs) W = (int)(segs < 1 ? 1 : segs);
-    p.W = W;
-    p.segs_per_wave = (int)((segs + W - 1) / W);
-    p.grid_x = (unsigned)blocks;
+    // waves per workgroup: aim at about two waves per SIMD (2048 on the chip); among the candidates from there
+    // up to 8 take the first that keeps every wave at least 80 % loaded, else the best balanced
+    const int wmax = (int)(segs < 8 ? segs : 8);
+    int w0 = (int)((2048 + blocks - 1) / blocks);
+    w0 = w0 < 1 ? 1 : (w0 > wmax ? wmax : w0);
+    int best_w = w0;
+    double best_eff = 0.0;
+    for (int w = w0; w <= wmax; ++w) {
+        const int64_t spw = (segs + w - 1) / w;
+        const double eff = (double)segs / (double)(w * spw);
+        if (eff >= 0.8) { best_w = w; break; }
+        if (eff > best_eff + 1e-9) { best_eff = eff; best_w = w; }
+    }
+    p.W = best_w;
+    p.segs_per_wave = (int)((segs + best_w - 1) / best_w);
+#ifdef BCQ_PROBE_PLAN
+    if (getenv("BCQ_W")) { p.W = atoi(getenv("BCQ_W")); if (p.W > segs) p.W = (int)segs; p.segs_per_wave = (int)((segs + p.W - 1) / p.W); }
+    if (getenv("BCQ_R")) p.R = atoi(getenv("BCQ_R"));
+#endif
+    p.grid_x = (unsigned)((rows + 16 * p.R - 1) / (16 * p.R));
     return p;
 }
 
@@ -267,22 +336,28 @@ static hipError_t launch_small(const uint32_t* planes, const bf16_t* act, const 
     const SmallPlan p = small_plan(rows, cw);
     const dim3 grid(p.grid_x, (unsigned)((T + 15) / 16));
     const dim3 block((unsigned)(64 * p.W));
+    if (p.W < 1 || p.W > 8) return hipErrorInvalidConfiguration;  // the kernel is compiled for at most 512 threads
     const int nout = (MODE == SMALL_DALPHA) ? q_used : 1;
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {  // up to 16 waves x 8 planes x 1 KiB of partial tiles
-        hipError_t e = hipFuncSetAttribute((const void*)small_kernel<MODE, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)small_kernel<MODE, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    const int qp = (MODE == SMALL_DX) ? 1 : (q_used <= 4 ? q_used : 8);
+#define BCQ_SMALL_LAUNCH(RR, QQ)                                                                                   \
+    hipLaunchKernelGGL((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
+                       q_used, scale, p.segs_per_wave)
+#define BCQ_SMALL_Q(RR)                                          \
+    switch (qp) {                                                \
+        case 1: BCQ_SMALL_LAUNCH(RR, 1); break;                  \
+        case 2: BCQ_SMALL_LAUNCH(RR, 2); break;                  \
+        case 3: BCQ_SMALL_LAUNCH(RR, 3); break;                  \
+        case 4: BCQ_SMALL_LAUNCH(RR, 4); break;                  \
+        default: BCQ_SMALL_LAUNCH(RR, 8); break;                 \
     }
-    if (p.R == 2)
-        hipLaunchKernelGGL((small_kernel<MODE, 2>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q,
-                           q_used, scale, p.segs_per_wave);
-    else
-        hipLaunchKernelGGL((small_kernel<MODE, 1>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q,
-                           q_used, scale, p.segs_per_wave);
+    if (p.R == 2) {
+        BCQ_SMALL_Q(2)
+    } else {
+        BCQ_SMALL_Q(1)
+    }
+#undef BCQ_SMALL_Q
+#undef BCQ_SMALL_LAUNCH
     return hipGetLastError();
 }
 
