@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -116,6 +119,13 @@ def main():
                     events.append((op, L["kind"], a, b))
                 else:
                     run_op(L, op)
+
+    if args.calibrate_copy:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

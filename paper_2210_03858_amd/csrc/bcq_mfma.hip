@@ -38,6 +38,65 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ---------------------------------------------------------------------------------------------------------
+// Workgroup -> tile mapping.  Consecutive workgroup ids go round-robin over the 8 XCDs, each with its own L2.
+// The tile grid is cut into super-blocks of a x b tiles; all workgroups that run on one XCD at the same time
+// belong to one super-block, so that XCD's L2 fetches only a/tiles_m of the first operand and b/tiles_n of the
+// second instead of a whole operand.
+struct TileMap {
+    int tiles_m, tiles_n, a, b, sbm, sbn;
+};
+
+__device__ __forceinline__ bool map_tile(const TileMap& tm, int copies, int bid, int& copy, int& tile_m, int& tile_n) {
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int per = tm.a * tm.b;
+    const int sbg = (slot / per) * 8 + xcd;  // super-block index over all copies of the tile grid
+    const int within = slot % per;
+    const int nsb = tm.sbm * tm.sbn;
+    if (sbg >= nsb * copies) return false;
+    copy = sbg / nsb;
+    const int sb = sbg % nsb;
+    tile_m = (sb % tm.sbm) * tm.a + within % tm.a;
+    tile_n = (sb / tm.sbm) * tm.b + within / tm.a;
+    return tile_m < tm.tiles_m && tile_n < tm.tiles_n;
+}
+
+// Super-block shape: about `cap` tiles (what one XCD runs concurrently), minimising the bytes both operands bring
+// in, a * cost_m + b * cost_n.  Returns the number of workgroups to launch.
+static inline unsigned make_tile_map(int tiles_m, int tiles_n, int copies, int cap, double cost_m, double cost_n,
+                                     TileMap* out) {
+    // never make a super-block larger than one XCD's share of all tiles (copies = independent tile grids, e.g.
+    // token slices), or some XCDs would get no work
+    const long share = ((long)tiles_m * tiles_n * copies + 7) / 8;
+    if (cap > share) cap = (int)(share < 1 ? 1 : share);
+    int best_a = 1, best_b = 1;
+    double best = 1e300;
+    for (int a = 1; a <= tiles_m && a <= cap; ++a) {
+        for (int b = 1; b <= tiles_n && a * b <= cap; ++b) {
+            const int sbm = (tiles_m + a - 1) / a, sbn = (tiles_n + b - 1) / b;
+            const long nsb = (long)sbm * sbn * copies;
+            // work really done per XCD round, including empty slots of ragged super-blocks and idle XCDs
+            const double slots = (double)((nsb + 7) / 8) * 8 * a * b;
+            const double waste = slots / ((double)tiles_m * tiles_n * copies);
+            const double per_tile = (a * cost_m + b * cost_n) / ((double)a * b);
+            const double score = per_tile * waste * waste * waste;  // balance first, then operand traffic
+            if (score < best) {
+                best = score;
+                best_a = a;
+                best_b = b;
+            }
+        }
+    }
+    out->tiles_m = tiles_m;
+    out->tiles_n = tiles_n;
+    out->a = best_a;
+    out->b = best_b;
+    out->sbm = (tiles_m + best_a - 1) / best_a;
+    out->sbn = (tiles_n + best_b - 1) / best_b;
+    const int nsb = out->sbm * out->sbn * copies;
+    return (unsigned)(((nsb + 7) / 8) * 8 * best_a * best_b);
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // expand for the forward: columns of the GEMM = rows n of W, contraction = k.
 // thread = (c = n % 32, 8 consecutive k of one packed word) -> one 16-byte fragment slot.
 __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restrict__ packed,
@@ -136,20 +195,15 @@ struct GemmCfg {
 template <int TM, int TN>
 __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const u32x4* __restrict__ Bfrag, bf16_t* __restrict__ C, int64_t ldc,
-    int64_t M, int64_t NC, int64_t R, int64_t R16, int tiles_m, int tiles_n) {
+    int64_t M, int64_t NC, int64_t R, int64_t R16, TileMap tmap) {
     using Cfg = GemmCfg<TM, TN>;
     constexpr int STAGE_B = Cfg::STAGE_B;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous
-    // run of tiles that share weight columns so that its L2 sees every weight fragment once
-    const int total = tiles_m * tiles_n;
-    const int bid = blockIdx.x;
-    const int per_xcd = total / 8;
-    const int lid = (bid < per_xcd * 8) ? (bid % 8) * per_xcd + bid / 8 : bid;
-    const int tile_n = lid / tiles_m, tile_m = lid % tiles_m;
+    int tile_m, tile_n, copy_unused;
+    if (!map_tile(tmap, 1, blockIdx.x, copy_unused, tile_m, tile_n)) return;  // padding workgroup of the last round
     const int64_t m0 = (int64_t)tile_m * Cfg::BMT, n0 = (int64_t)tile_n * Cfg::BNT;
     const int64_t ct_count = (NC + 31) / 32;
 
@@ -348,8 +402,10 @@ static hipError_t launch_gemm_cfg(const bf16_t* A, int64_t lda, const u32x4* fra
         attr_set = true;
     }
     const int tiles_m = (int)((M + Cfg::BMT - 1) / Cfg::BMT), tiles_n = (int)((NC + Cfg::BNT - 1) / Cfg::BNT);
-    hipLaunchKernelGGL((gemm_kernel<TM, TN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), Cfg::LDS_B, st, A, lda,
-                       frag, C, ldc, M, NC, R, R16, tiles_m, tiles_n);
+    TileMap tmap;
+    const unsigned wgs = make_tile_map(tiles_m, tiles_n, 1, 32 * Cfg::OCC, (double)Cfg::BMT, (double)Cfg::BNT, &tmap);
+    hipLaunchKernelGGL((gemm_kernel<TM, TN>), dim3(wgs), dim3(256), Cfg::LDS_B, st, A, lda, frag, C, ldc, M, NC, R, R16,
+                       tmap);
     return hipGetLastError();
 }
 
@@ -447,12 +503,14 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
                                                         const u32x4* __restrict__ Gfrag, int64_t T16,
                                                         const uint32_t* __restrict__ packed,
                                                         float* __restrict__ part, int64_t T, int64_t N, int64_t K,
-                                                        int q_train, int tiles_k, int tiles_n, int64_t tokens_per_split) {
+                                                        int q_train, TileMap tmap, int splits,
+                                                        int64_t tokens_per_split) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;  // wm: k half, wn: n half
-    const int tile_k = blockIdx.x % tiles_k, tile_n = blockIdx.x / tiles_k;
-    const int split = blockIdx.y;
+    const int tiles_k = tmap.tiles_m;
+    int split, tile_k, tile_n;
+    if (!map_tile(tmap, splits, blockIdx.x, split, tile_k, tile_n)) return;
     const int64_t k0 = (int64_t)tile_k * DA_TILE, n0 = (int64_t)tile_n * DA_TILE;
     const int64_t t_begin = (int64_t)split * tokens_per_split;  // a multiple of 64
     const int64_t t_end = (t_begin + tokens_per_split < T) ? t_begin + tokens_per_split : T;
@@ -672,13 +730,15 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    dim3 grid((unsigned)(pl.tiles_k * pl.tiles_n), (unsigned)pl.splits);
+    TileMap tmap;
+    const unsigned wgs = make_tile_map(pl.tiles_k, pl.tiles_n, pl.splits, 32, 1.0, 1.0, &tmap);
+    dim3 grid(wgs);
     if (pl.xg)
         hipLaunchKernelGGL(dalpha_kernel<true>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
-                           T, N, K, q_train, pl.tiles_k, pl.tiles_n, pl.per_split);
+                           T, N, K, q_train, tmap, pl.splits, pl.per_split);
     else
         hipLaunchKernelGGL(dalpha_kernel<false>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
-                           T, N, K, q_train, pl.tiles_k, pl.tiles_n, pl.per_split);
+                           T, N, K, q_train, tmap, pl.splits, pl.per_split);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)q_train * N;
