@@ -107,10 +107,11 @@ def main():
         else:
             bcq.bcq_linear_bwd_alpha(L["packed"], L["x"], L["dy"], dalpha=L["da"], workspace=L["ws"][3])
 
-    def step(events=None):
+    def step(events=None, only=None):
+        """One pass of the hot path.  With `events`, HIP events bracket every op (or only the ops of family `only`)."""
         for L in layers:
             for op in ops:
-                if events is not None:
+                if events is not None and (only is None or op == only):
                     a = torch.cuda.Event(enable_timing=True)
                     b = torch.cuda.Event(enable_timing=True)
                     a.record()
@@ -120,22 +121,22 @@ def main():
                 else:
                     run_op(L, op)
 
-    if args.calibrate_copy:
-        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
-        step()
+    # ---------------- warm-up: every op bracketed by events -> per-op table and the dominant op family
+    warm_events = []
+    for _ in range(max(args.warmup, 1)):
+        step(warm_events)
     torch.cuda.synchronize()
+    fam_ms = {}
+    for op, kind, a, b in warm_events[-len(ops) * len(layers):]:
+        fam_ms[op] = fam_ms.get(op, 0.0) + a.elapsed_time(b)
+    dom = max(fam_ms, key=lambda k: fam_ms[k])
 
-    # ---------------- timed region: exactly --steps steps
+    # ---------------- timed region: exactly --steps steps; events only around the dominant family's launches
+    # (an event pair costs a few microseconds of GPU idle time, so bracketing all twelve ops would slow the step)
     events = None if args.no_events else []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(events)
+        step(events, only=dom)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -144,27 +145,25 @@ def main():
     flops_step = 3.0 * sum(flops_layer.values())
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---------------- per-op timing -> dominant kernel family and its roofline
+    # ---------------- roofline of the dominant op family (timed region) and per-op table (warm-up steps)
     per_op = {}
+    for op, kind, a, b in warm_events[-len(ops) * len(layers):]:  # last warm-up step (the first pays one-time set-up)
+        d = per_op.setdefault(op, dict(ms=0.0, flops=0.0))
+        d["ms"] += a.elapsed_time(b)
+        d["flops"] += flops_layer[kind]
+    per_op = {k: {"ms_per_step": round(v["ms"], 4),
+                  "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3)} for k, v in per_op.items()}
     roofline = None
     if events:
-        for op, kind, a, b in events:
-            d = per_op.setdefault(op, dict(ms=0.0, launches=0, flops=0.0))
-            d["ms"] += a.elapsed_time(b)
-            d["launches"] += 1
-            d["flops"] += flops_layer[kind]
-        dom = max(per_op, key=lambda k: per_op[k]["ms"])
-        d = per_op[dom]
-        achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
+        ms = sum(a.elapsed_time(b) for _, _, a, b in events)
+        fl = sum(flops_layer[kind] for _, kind, _, _ in events)
+        achieved = fl / (ms * 1e-3) / 1e12
         main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
         roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
-                    "traffic": None, "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
-                    "launches": d["launches"],
+                    "traffic": None, "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
                     "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
-        per_op = {k: {"ms_per_step": round(v["ms"] / args.steps, 4),
-                      "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3)} for k, v in per_op.items()}
 
     # ---------------- CPU oracle on a bounded sample of the same workload
     cpu = None
