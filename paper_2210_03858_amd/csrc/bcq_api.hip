@@ -192,7 +192,7 @@ bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t
     if (workspace && packed_t && small_bwd_input_ok(T, N, dtype))
         return done(bcq::launch_bwd_input_small(packed_t, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
     if (workspace && mfma_bwd_input_ok(T, N, dtype))
-        return done(bcq::launch_bwd_input_mfma(packed, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
+        return done(bcq::launch_bwd_input_mfma(packed, packed_t, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
     return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, q, dx, (hipStream_t)stream));
 }
 

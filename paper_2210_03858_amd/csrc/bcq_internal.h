@@ -51,8 +51,8 @@ size_t mfma_fwd_workspace(int64_t N, int64_t K);
 size_t mfma_bwd_input_workspace(int64_t N, int64_t K);
 hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
                            int64_t K, int q, void* y, void* workspace, hipStream_t st);
-hipError_t launch_bwd_input_mfma(const uint32_t* packed, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q, void* dx, void* workspace, hipStream_t st);
+hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_t, const float* alpha, const void* dy,
+                                 int64_t T, int64_t N, int64_t K, int q, void* dx, void* workspace, hipStream_t st);
 size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q);
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                  int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,

@@ -97,82 +97,86 @@ static inline unsigned make_tile_map(int tiles_m, int tiles_n, int copies, int c
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// 32 fp32 sums -> 16 bf16 pairs -> four 16-byte fragment slots of 8 contraction indices each
+__device__ __forceinline__ void store_word_frags(const float (&s)[32], u32x4* __restrict__ frag, int64_t block0, int c) {
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg) {
+        u32x4 v;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) v[p] = pack_bf16x2(s[8 * gg + 2 * p], s[8 * gg + 2 * p + 1]);
+        frag[(block0 + (gg >> 1)) * 64 + c + 32 * (gg & 1)] = v;
+    }
+}
+
 // expand for the forward: columns of the GEMM = rows n of W, contraction = k.
-// thread = (c = n % 32, 8 consecutive k of one packed word) -> one 16-byte fragment slot.
+// thread = (c = n % 32, one packed word = 32 columns k) -> four 16-byte fragment slots.
 __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ alpha, int64_t N, int64_t K,
                                                          int q, int64_t R16 /* padded K / 16 */,
-                                                         uint4* __restrict__ frag) {
+                                                         u32x4* __restrict__ frag) {
     const int c = threadIdx.x & 31;
     const int64_t ct = blockIdx.x;
     const int64_t n = ct * 32 + c;
     const int64_t Kw = K / 32;
-    const int64_t slot = (int64_t)blockIdx.y * 8 + (threadIdx.x >> 5);  // = ks * 2 + g, 8 columns each
-    if (slot >= R16 * 2) return;
-    const int64_t w = slot >> 2;
-    const int sh = (int)(slot & 3) * 8;
+    const int64_t w = (int64_t)blockIdx.y * 8 + (threadIdx.x >> 5);
+    if (w * 2 >= R16) return;
     const bool live = (n < N) && (w < Kw);
-    float a[8];
-    uint32_t bits[8];
+    float s[32];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (i < q && live) ? alpha[(int64_t)i * N + n] : 0.f;
-        bits[i] = (i < q && live) ? (packed[((int64_t)i * N + n) * Kw + w] >> sh) : 0u;
+    for (int e = 0; e < 32; ++e) s[e] = 0.f;
+    for (int i = 0; i < q; ++i) {
+        const float a = live ? alpha[(int64_t)i * N + n] : 0.f;
+        const uint32_t bits = live ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) s[e] += ((bits >> e) & 1u) ? a : -a;
     }
-    uint32_t out[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        float v[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int j = p * 2 + e;
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i < q) s += ((bits[i] >> j) & 1u) ? a[i] : -a[i];
-            v[e] = s;
-        }
-        out[p] = pack_bf16x2(v[0], v[1]);
-    }
-    frag[(ct * R16 + (slot >> 1)) * 64 + c + 32 * (int)(slot & 1)] = make_uint4(out[0], out[1], out[2], out[3]);
+    store_word_frags(s, frag, ct * R16 + 2 * w, c);
 }
 
-// expand for the input gradient: columns of the GEMM = columns k of W, contraction = n (transposed use of
-// the canonical words: the 32 lanes of a column tile share one word and each takes its own bit).
-__global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restrict__ packed,
+// expand for the input gradient: columns of the GEMM = columns k of W, contraction = n.  Reads the transposed
+// twin when the caller has one (one word = 32 consecutive n of this thread's column), else the canonical words
+// (the 32 lanes of a column tile share a word and each takes its own bit).  The scales of the block's 256 rows
+// pass through LDS.
+template <bool TWIN>
+__global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restrict__ planes,
                                                          const float* __restrict__ alpha, int64_t N, int64_t K,
                                                          int q, int64_t R16 /* padded N / 16 */,
-                                                         uint4* __restrict__ frag) {
-    const int c = threadIdx.x & 31;
+                                                         u32x4* __restrict__ frag) {
+    __shared__ float sa[8][256];
+    const int c = threadIdx.x & 31, vl = threadIdx.x >> 5;
     const int64_t ct = blockIdx.x;  // K / 32 column tiles, exactly one packed word wide
-    const int64_t Kw = K / 32;
-    const int64_t slot = (int64_t)blockIdx.y * 8 + (threadIdx.x >> 5);  // = ks * 2 + g
-    if (slot >= R16 * 2) return;
-    const int64_t ks = slot >> 1;
-    const int g = (int)(slot & 1);
-    uint32_t out[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        float v[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int64_t n = ks * 16 + g * 8 + p * 2 + e;
-            float s = 0.f;
-            if (n < N) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    if (i < q) {
-                        const float a = alpha[(int64_t)i * N + n];
-                        const uint32_t b = packed[((int64_t)i * N + n) * Kw + ct];
-                        s += ((b >> c) & 1u) ? a : -a;
-                    }
-                }
-            }
-            v[e] = s;
-        }
-        out[p] = pack_bf16x2(v[0], v[1]);
+    const int64_t Kw = K / 32, Nw = N / 32;
+    const int64_t n_blk = (int64_t)blockIdx.y * 256;
+    for (int i = 0; i < q; ++i) {
+        const int64_t n = n_blk + threadIdx.x;
+        sa[i][threadIdx.x] = (n < N) ? alpha[(int64_t)i * N + n] : 0.f;  // rows beyond N expand to zero
     }
-    frag[(ct * R16 + ks) * 64 + c + 32 * g] = make_uint4(out[0], out[1], out[2], out[3]);
+    __syncthreads();
+    const int64_t v = (int64_t)blockIdx.y * 8 + vl;  // word index along n
+    if (v * 2 >= R16) return;
+    const int64_t k = ct * 32 + c;
+    float s[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) s[e] = 0.f;
+    for (int i = 0; i < q; ++i) {
+        uint32_t bits = 0u;
+        if (TWIN) {
+            bits = (v < Nw) ? planes[((int64_t)i * K + k) * Nw + v] : 0u;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                const int64_t n = v * 32 + e;
+                const uint32_t wv = (n < N) ? planes[((int64_t)i * N + n) * Kw + ct] : 0u;
+                bits |= ((wv >> c) & 1u) << e;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const float a = sa[i][vl * 32 + e];
+            s[e] += ((bits >> e) & 1u) ? a : -a;
+        }
+    }
+    store_word_frags(s, frag, ct * R16 + 2 * v, c);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -422,18 +426,23 @@ hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const voi
                            int64_t K, int q, void* y, void* workspace, hipStream_t st) {
     const int64_t R16 = round_up(K, BK) / 16;
     const int64_t ct = (N + 31) / 32;
-    dim3 grid((unsigned)ct, (unsigned)((R16 * 2 + 7) / 8));
-    hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16, (uint4*)workspace);
+    dim3 grid((unsigned)ct, (unsigned)((R16 / 2 + 7) / 8));
+    hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16, (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_gemm((const bf16_t*)x, K, (const u32x4*)workspace, (bf16_t*)y, N, T, N, K, R16, st);
 }
 
-hipError_t launch_bwd_input_mfma(const uint32_t* packed, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
+hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_t, const float* alpha, const void* dy,
+                                 int64_t T, int64_t N, int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
     const int64_t R16 = round_up(N, BK) / 16;
-    dim3 grid((unsigned)(K / 32), (unsigned)((R16 * 2 + 7) / 8));
-    hipLaunchKernelGGL(expand_bwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16, (uint4*)workspace);
+    dim3 grid((unsigned)(K / 32), (unsigned)((R16 / 2 + 7) / 8));
+    if (packed_t && N % 32 == 0)
+        hipLaunchKernelGGL(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, q, R16,
+                           (u32x4*)workspace);
+    else
+        hipLaunchKernelGGL(expand_bwd_kernel<false>, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16,
+                           (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_gemm((const bf16_t*)dy, N, (const u32x4*)workspace, (bf16_t*)dx, K, T, K, N, R16, st);

@@ -160,7 +160,7 @@ def test_config1_fp32_full(bcq, oracle):
                                      (300, 544, 1056, 3), (17, 35, 32, 8)])
 def test_small_shapes_ragged(bcq, oracle, dtype, T, N, K, q):
     """Shapes that span several tiles with ragged tails in T, N and K; with and without workspace / twin."""
-    for workspace, twin in ((False, False), (True, True)):
+    for workspace, twin in ((False, False), (True, True), (True, False)):
         _run_layer(bcq, oracle, 3, "out", T, N, K, q, dtype, workspace=workspace, twin=twin)
 
 
