@@ -322,7 +322,16 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     // whole rows of 64 TN bytes are contiguous.
     constexpr int EROW = Cfg::EPI_ROWB;
 #ifdef BCQ_PROBE_NO_STORE
-    if (acc[0][0][0] != 123.456f) return;
+    {
+        float keep = 0.f;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) keep += acc[i][j][v];
+        if (keep != 123.456f) return;
+    }
 #endif
     const bool vec_ok = (ldc % 8 == 0);
     if (vec_ok) {
@@ -506,7 +515,9 @@ __global__ __launch_bounds__(256) void transpose_frag_kernel(const bf16_t* __res
     for (int c = 0; c < 8; ++c) frag[(ct * T16 + ks) * 64 + (c0 % 32) + c + 32 * g] = out[c];
 }
 
-template <bool XG>  // XG: x comes as fragments from global memory and dy through LDS; otherwise the reverse
+// XG: x comes as fragments from global memory and dy through LDS; otherwise the reverse.
+// QT: planes summed in the epilogue (q_train rounded up to 1, 2, 3, 4 or 8; extra planes are computed, not stored).
+template <bool XG, int QT>
 __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict__ L /* activation through LDS */,
                                                         int64_t ldl, int64_t lcols,
                                                         const u32x4* __restrict__ Gfrag, int64_t T16,
@@ -624,41 +635,76 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
     __syncthreads();
 
 #ifdef BCQ_PROBE_NO_EPI
-    if (acc[0][0][0] != 123.456f) return;
+    {
+        float keep = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) keep += acc[i][j][v];
+        if (keep != 123.456f) return;
+    }
 #endif
-    // epilogue: signed sums over this wave's 128 k for each plane; lane owns n = n_base + j*32 + lane%32
+    // epilogue: signed sums over this wave's 128 k for each plane; lane owns n = n_base + j*32 + lane%32.
+    // All packed words of all trained planes are requested first (one memory latency instead of one per plane);
+    // a sign is applied by XOR-ing the (inverted) plane bit into the fp32 sign bit: shift, bit-op, add per value.
     float* red = reinterpret_cast<float*>(smem);  // [plane][wm][256 n]
     const int64_t Kw = K / 32;
-    for (int p = 0; p < q_train; ++p) {
-        uint32_t words[4][4];
+    uint32_t words[QT][4][4];  // [plane][k tile][n tile], already inverted and shifted to this lane's rows
+    const int64_t kt0 = (k0 + wm * 128) / 32;                      // first of this wave's four k tiles
+    const bool quad = (kt0 + 3 < Kw) && ((Kw & 3) == 0);           // one aligned 16-byte load per row and plane
+#pragma unroll
+    for (int p = 0; p < QT; ++p) {
+        const int pc = p < q_train ? p : q_train - 1;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t n = n0 + wn * 128 + j * 32 + (lane & 31);
             const int64_t nc = n < N ? n : N - 1;
+            const uint32_t* prow = packed + ((int64_t)pc * N + nc) * Kw;
+            u32x4 w4;
+            if (quad) {
+                w4 = *reinterpret_cast<const u32x4*>(prow + kt0);
+            } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int64_t kt = (k0 + wm * 128 + i * 32) / 32;
-                kt = kt < Kw ? kt : Kw - 1;  // tiles beyond K hold zero accumulators (zero or unused fragments)
-                words[i][j] = packed[((int64_t)p * N + nc) * Kw + kt] >> (4 * (lane >> 5));
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t kt = kt0 + i < Kw ? kt0 + i : Kw - 1;  // tiles beyond K hold zero accumulators
+                    w4[i] = prow[kt];
+                }
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) words[p][i][j] = ~(w4[i] >> (4 * (lane >> 5)));
         }
+    }
+    // every accumulator is read once and added, with its sign, into the sums of all planes
+    float sums[QT][4];  // [plane][n tile]
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float s = 0.f;
+    for (int p = 0; p < QT; ++p)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bool live = (k0 + wm * 128 + i * 32) < K;
+        for (int j = 0; j < 4; ++j) sums[p][j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if ((k0 + wm * 128 + i * 32) < K) {  // uniform: tiles beyond K hold nothing
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int bit = 8 * (v >> 2) + (v & 3);
-                    const float a = live ? acc[i][j][v] : 0.f;
-                    s += ((words[i][j] >> bit) & 1u) ? a : -a;
+                    const uint32_t a = __float_as_uint(acc[i][j][v]);
+#pragma unroll
+                    for (int p = 0; p < QT; ++p)  // sign bit set where the plane bit is 0 (-1): words are inverted
+                        sums[p][j] += __uint_as_float(a ^ ((words[p][i][j] << (31 - bit)) & 0x80000000u));
                 }
-            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < QT; ++p)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float s = sums[p][j];
             s += __shfl_xor(s, 32);
             if (lane < 32) red[(p * 2 + wm) * 256 + wn * 128 + j * 32 + lane] = s;
         }
-    }
     __syncthreads();
     const int64_t part_id = (int64_t)split * tiles_k + tile_k;
     for (int p = 0; p < q_train; ++p) {
@@ -696,7 +742,7 @@ static DalphaPlan dalpha_plan(int64_t T, int64_t N, int64_t K, int q) {
     pl.tiles_k = (int)((K + DA_TILE - 1) / DA_TILE);
     pl.tiles_n = (int)((N + DA_TILE - 1) / DA_TILE);
     const int64_t tiles = (int64_t)pl.tiles_k * pl.tiles_n;
-    int64_t s = (256 + tiles - 1) / tiles;            // one workgroup per compute unit
+    int64_t s = tiles >= 256 ? 1 : 256 / tiles;       // one round of workgroups on the 256 compute units
     const int64_t max_s = (T + 255) / 256;            // at least 256 tokens (4 steps) per slice
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
@@ -718,15 +764,7 @@ size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q) {
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                  int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
                                  hipStream_t st) {
-    static bool attr_set = false;
     const int lds = 2 * DA_STAGE;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)dalpha_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)dalpha_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const DalphaPlan pl = dalpha_plan(T, N, K, q);
     u32x4* frag = reinterpret_cast<u32x4*>(workspace);
     float* part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.frag_bytes);
@@ -742,12 +780,34 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     TileMap tmap;
     const unsigned wgs = make_tile_map(pl.tiles_k, pl.tiles_n, pl.splits, 32, 1.0, 1.0, &tmap);
     dim3 grid(wgs);
-    if (pl.xg)
-        hipLaunchKernelGGL(dalpha_kernel<true>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
-                           T, N, K, q_train, tmap, pl.splits, pl.per_split);
-    else
-        hipLaunchKernelGGL(dalpha_kernel<false>, grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, part,
-                           T, N, K, q_train, tmap, pl.splits, pl.per_split);
+    const int qt = q_train <= 4 ? q_train : 8;
+#define BCQ_DA_LAUNCH(XGV, QTV)                                                                                       \
+    {                                                                                                                 \
+        static bool attr_set = false;                                                                                 \
+        if (!attr_set) {                                                                                              \
+            hipError_t ea = hipFuncSetAttribute((const void*)dalpha_kernel<XGV, QTV>,                                  \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);                     \
+            if (ea != hipSuccess) return ea;                                                                          \
+            attr_set = true;                                                                                          \
+        }                                                                                                             \
+        hipLaunchKernelGGL((dalpha_kernel<XGV, QTV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, \
+                           part, T, N, K, q_train, tmap, pl.splits, pl.per_split);                                    \
+    }
+#define BCQ_DA_Q(XGV)                                  \
+    switch (qt) {                                      \
+        case 1: BCQ_DA_LAUNCH(XGV, 1) break;           \
+        case 2: BCQ_DA_LAUNCH(XGV, 2) break;           \
+        case 3: BCQ_DA_LAUNCH(XGV, 3) break;           \
+        case 4: BCQ_DA_LAUNCH(XGV, 4) break;           \
+        default: BCQ_DA_LAUNCH(XGV, 8) break;          \
+    }
+    if (pl.xg) {
+        BCQ_DA_Q(true)
+    } else {
+        BCQ_DA_Q(false)
+    }
+#undef BCQ_DA_Q
+#undef BCQ_DA_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)q_train * N;
