@@ -35,6 +35,12 @@ def parse():
     ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from one captured HIP graph (default for fewer than 32 tokens, where "
+                         "launching from Python would otherwise bound the step)")
+    ap.add_argument("--replicas", type=int, default=0,
+                    help="independent copies of the layer stack (own weights), so that the packed planes streamed per "
+                         "step exceed the 256 MB Infinity Cache; default 1, or enough for 512 MB when tokens < 32")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -66,13 +72,18 @@ def main():
     code = bcq.binding.BCQ_BF16 if dtype == "bf16" else bcq.binding.BCQ_F32
     kinds = cfg["kinds"]
 
+    small = T < 32            # streaming regime: bound by HBM, measured over a stack of distinct layers
+    use_graph = args.graph or small
+    block_packed = sum(synth.layer_shape(h, k)[0] * synth.layer_shape(h, k)[1] for k in kinds) * q // 8
+    replicas = args.replicas or (max(1, -(-(512 << 20) // block_packed)) if small else 1)
+
     # ---------------- one-time setup: synthetic weights -> greedy BCQ on the GPU, twin, activations
     layers = []
     setup_ms = {"quantize": 0.0, "pack_transposed": 0.0}
     weights_total = 0
-    for kind in kinds:
+    for rep, kind in [(r, k) for r in range(replicas) for k in kinds]:
         N, K = synth.layer_shape(h, kind)
-        W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])).cuda()
+        W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"], extra=rep)).cuda()
         e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
         bcq.bcq_quantize(W, q)  # warm
         e0.record()
@@ -126,6 +137,13 @@ def main():
     for _ in range(max(args.warmup, 1)):
         step(warm_events)
     torch.cuda.synchronize()
+    graph = None
+    if use_graph:  # the library neither allocates nor memsets, so a step can be captured as it is
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
     fam_ms = {}
     for op, kind, a, b in warm_events[-len(ops) * len(layers):]:
         fam_ms[op] = fam_ms.get(op, 0.0) + a.elapsed_time(b)
@@ -133,10 +151,13 @@ def main():
 
     # ---------------- timed region: exactly --steps steps; events only around the dominant family's launches
     # (an event pair costs a few microseconds of GPU idle time, so bracketing all twelve ops would slow the step)
-    events = None if args.no_events else []
+    events = None if (args.no_events or graph is not None) else []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(events, only=dom)
+        if graph is not None:
+            graph.replay()
+        else:
+            step(events, only=dom)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -164,6 +185,21 @@ def main():
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
                     "traffic": None, "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
                     "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
+
+    if small:
+        # streaming regime: the planes are the only large operand; algorithmic bytes of one step
+        sz = 2 if dtype == "bf16" else 4
+        bytes_step = 0.0
+        for L in layers:
+            planes_b = q * L["N"] * L["K"] / 8
+            bytes_step += 3 * planes_b + 2 * 4 * q * L["N"] + 2 * sz * T * (L["K"] + L["N"]) + sz * T * (L["K"] + L["N"])
+        achieved = bytes_step / (ms_per_step * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "small_kernel (fwd, dalpha, dx modes; whole captured step)",
+                    "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(achieved / PEAK_HBM_GBS, 5), "traffic": None,
+                    "packed_plane_GBps": round(3 * sum(q * L["N"] * L["K"] / 8 for L in layers) / (ms_per_step * 1e-3) / 1e9, 1),
+                    "algorithmic": "per op and layer: q*N*K/8 plane bytes + 4*q*N + activations; planes are read once "
+                                   "by each of fwd, dx, dalpha"}
 
     # ---------------- CPU oracle on a bounded sample of the same workload
     cpu = None
@@ -205,7 +241,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s activations, T=%d tokens; fwd+dx+dalpha"
                                % (args.config, h, "/".join(kinds), q, dtype, T),
-                   "h": h, "q": q, "tokens": T, "weights_per_block": weights_total},
+                   "h": h, "q": q, "tokens": T, "weights_per_block": weights_total // replicas,
+                   "layer_stack_replicas": replicas, "hip_graph": graph is not None},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_op": per_op,
