@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 
+# HBM-side bytes per launch of the dominant kernel of the default workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy); see
+# profiles/bench_config2_hbm_traffic.md for the commands and the table.  Not measured live: null for other workloads.
+PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 6.3e7, (2, 4096, 4, "bwd_input"): 7.1e7}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -132,6 +137,13 @@ def main():
                 else:
                     run_op(L, op)
 
+    if args.calibrate_copy:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---------------- warm-up: every op bracketed by events -> per-op table and the dominant op family
     warm_events = []
     for _ in range(max(args.warmup, 1)):
@@ -183,7 +195,8 @@ def main():
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
         roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
-                    "traffic": None, "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
+                    "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)),
+                    "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
                     "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
 
     if small:
