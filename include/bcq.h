@@ -27,7 +27,7 @@
  *     enables the fastest path; a non-NULL workspace smaller than that is BCQ_ERR_WORKSPACE.
  *   - Return value: BCQ_OK or the first problem found; nothing is enqueued unless BCQ_OK.
  *     Order of checks: NULL pointers, shapes, dtype, alignment, workspace, device.
- *   - Limits: 1 <= q <= 8; K % 32 == 0; N, K, T >= 1; N*K and T*max(N,K) below 2^40.
+ *   - Limits: 1 <= q <= 8; K % 32 == 0; 1 <= N, K <= 2^17; 1 <= T <= 2^24; N*K and T*max(N,K) at most 2^40.
  *   - No global state besides per-device capability caches; calls on different streams may overlap
  *     as long as their outputs and workspaces do not alias.
  */
@@ -109,8 +109,10 @@ bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void
                           void* stream);
 
 /* Input gradient (Eq. 3): dx[t][k] = sum_n dy[t][n] * sum_i alpha_i[n] * B_i[n][k].
- *   packed [q][N][K/32] in; packed_t [q][K][N/32] in, may be NULL (then a slower path that reads only
- *   `packed` is used; non-NULL needs N % 32 == 0); alpha [q][N] in; dy [T][N] `dtype` in; dx [T][K] `dtype` out. */
+ *   packed [q][N][K/32] in; packed_t [q][K][N/32] in, may be NULL (non-NULL needs N % 32 == 0); alpha [q][N] in;
+ *   dy [T][N] `dtype` in; dx [T][K] `dtype` out.
+ * Below 32 tokens the fast path streams the twin and needs BOTH packed_t and the workspace; from 32 tokens on it
+ * needs the workspace only and uses packed_t when given.  Without them a slower path reads `packed`. */
 bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
                                 const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
                                 void* workspace, size_t workspace_bytes, void* stream);
