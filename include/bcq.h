@@ -102,7 +102,8 @@ bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int
                                void* stream);
 
 /* Forward (Eq. 2): y[t][n] = sum_i alpha_i[n] * sum_k B_i[n][k] * x[t][k], fp32 accumulation,
- * result rounded to `dtype` (bf16: round to nearest even).  W is never materialised in memory.
+ * result rounded to `dtype` (bf16: round to nearest even).  The dequantised W exists at most as a transient bf16
+ * copy of this one layer inside the caller's workspace (large-token path); without a workspace it never exists.
  *   packed [q][N][K/32] in; alpha [q][N] fp32 in; x [T][K] `dtype` in; y [T][N] `dtype` out. */
 bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
                           int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,

@@ -22,9 +22,6 @@ namespace bcq {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int ROWB = BK * 2 + 16;         // bytes per LDS row of the activation tile (padded)
-constexpr int STAGE = BM * ROWB;          // bytes per LDS stage
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -181,7 +178,7 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
 
 // ---------------------------------------------------------------------------------------------------------
 // C[M][NC] = A[M][R] * Bfrag, A row-major bf16 with leading dimension lda, Bfrag in fragment order with R16
-// slices per column tile (R16 * 16 >= R, a multiple of BK), C row-major bf16 with leading dimension ldc.
+// slices per column tile (R16 * 16 >= R, a multiple of 128), C row-major bf16 with leading dimension ldc.
 // Workgroup tile (64 TM) x (64 TN), 4 waves in a 2 x 2 grid, each wave TM x TN MFMA tiles.
 // The weight fragment is the first MFMA operand, so one lane ends up with 4 consecutive output columns of
 // one token.  Out-of-range rows, chunks and column tiles are clamped to valid addresses instead of branching:
@@ -189,7 +186,10 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
 template <int TM, int TN>
 struct GemmCfg {
     static constexpr int BMT = 64 * TM, BNT = 64 * TN;
-    static constexpr int STAGE_B = BMT * ROWB;                 // one activation stage
+    static constexpr int BKC = (TM * TN <= 4) ? 128 : 64;      // contraction per K-step: small tiles take longer steps
+    static constexpr int KS = BKC / 16;                        // 16-slices per K-step
+    static constexpr int ROWBC = BKC * 2 + 16;                 // LDS row of the activation tile, padded by 16 B
+    static constexpr int STAGE_B = BMT * ROWBC;                // one activation stage
     static constexpr int EPI_ROWB = 64 * TN + 8;               // epilogue row: 32 TN columns of bf16 + pad
     static constexpr int EPI_B = 4 * 64 * EPI_ROWB;            // 4 waves x 64 tokens
     static constexpr int LDS_B = (2 * STAGE_B > EPI_B) ? 2 * STAGE_B : EPI_B;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const u32x4* __restrict__ Bfrag, bf16_t* __restrict__ C, int64_t ldc,
     int64_t M, int64_t NC, int64_t R, int64_t R16, TileMap tmap) {
     using Cfg = GemmCfg<TM, TN>;
-    constexpr int STAGE_B = Cfg::STAGE_B;
+    constexpr int STAGE_B = Cfg::STAGE_B, ROWBC = Cfg::ROWBC, KS = Cfg::KS, BKC = Cfg::BKC;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -219,13 +219,13 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // activation tile: 64 TM rows x 8 chunks of 16 B; thread handles chunk lc of rows lr + 32 * j
-    constexpr int NA = 2 * TM;
-    const int lc = tid & 7, lr = tid >> 3;
+    // activation tile: 64 TM rows x CPR chunks of 16 B; thread handles chunk lc of rows lr + RSTEP * j
+    constexpr int CPR = BKC / 8, RSTEP = 256 / CPR, NA = 64 * TM / RSTEP;
+    const int lc = tid % CPR, lr = tid / CPR;
     const bf16_t* arow[NA];
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
-        int64_t row = m0 + lr + 32 * j;
+        int64_t row = m0 + lr + RSTEP * j;
         row = row < M ? row : M - 1;
         arow[j] = A + row * lda;
     }
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     auto store_a = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < NA; ++j)
-            *reinterpret_cast<u32x4*>(smem + buf * STAGE_B + (lr + 32 * j) * ROWB + lc * 16) = areg[j];
+            *reinterpret_cast<u32x4*>(smem + buf * STAGE_B + (lr + RSTEP * j) * ROWBC + lc * 16) = areg[j];
     };
 
     // weight fragments of this wave: column tiles ct0 .. ct0+TN-1
@@ -255,20 +255,20 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
         ct = ct < ct_count ? ct : ct_count - 1;
         bptr[j] = Bfrag + ct * R16 * 64 + lane;
     }
-    u32x4 b[4][TN];  // [kk][j]; slot kk is refilled for the next K-step right after its MFMAs are issued
+    u32x4 b[KS][TN];  // [kk][j]; slot kk is refilled for the next K-step right after its MFMAs are issued
     auto load_b = [&](int kk, int64_t step) {
 #ifdef BCQ_PROBE_NO_B
         if (step > 0) return;
 #endif
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[kk][j] = bptr[j][(step * 4 + kk) * 64];
+        for (int j = 0; j < TN; ++j) b[kk][j] = bptr[j][(step * KS + kk) * 64];
     };
     bf16x8 xf[2][TM];  // activation fragments of two consecutive 16-slices
     auto read_x = [&](int buf, int kk) {
         const unsigned char* sa =
-            smem + buf * STAGE_B + (wm * 32 * TM + (lane & 31)) * ROWB + (lane >> 5) * 16 + kk * 32;
+            smem + buf * STAGE_B + (wm * 32 * TM + (lane & 31)) * ROWBC + (lane >> 5) * 16 + kk * 32;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWB);
+        for (int i = 0; i < TM; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWBC);
     };
     auto mfma_slice = [&](int kk) {
 #pragma unroll
@@ -278,26 +278,26 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), xf[kk & 1][i], acc[j][i], 0, 0, 0);
     };
 
-    const int64_t steps = R16 * 16 / BK;
+    const int64_t steps = R16 * 16 / BKC;
     const int64_t last = steps - 1;
     load_a(0);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) load_b(kk, 0);
+    for (int kk = 0; kk < KS; ++kk) load_b(kk, 0);
     store_a(0);
     __syncthreads();
     read_x(0, 0);
 
-    // One K-step = four 16-slices.  Slices 0..2: issue the LDS reads of the next slice, the MFMAs of this one,
+    // One K-step = KS 16-slices.  All but the last: issue the LDS reads of the next slice, the MFMAs of this one,
     // then refill this slice's weight registers for the next K-step (a full step of latency cover).  The LDS
-    // hand-over to the next stage (write, barrier, first fragment read) sits BEFORE the MFMAs of slice 3, whose
-    // operands are already in registers, so the matrix pipe stays busy across the barrier.
+    // hand-over to the next stage (write, barrier, first fragment read) sits BEFORE the MFMAs of the last slice,
+    // whose operands are already in registers, so the matrix pipe stays busy across the barrier.
     for (int64_t s = 0; s < steps; ++s) {
         const int buf = (int)(s & 1);
         const int64_t nx = s < last ? s + 1 : last;
-        load_a(nx * BK);
+        load_a(nx * BKC);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 0; kk < KS - 1; ++kk) {
             read_x(buf, kk + 1);
             mfma_slice(kk);
             load_b(kk, nx);
@@ -310,8 +310,8 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
         __syncthreads();
         read_x(buf ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_slice(3);
-        load_b(3, nx);
+        mfma_slice(KS - 1);
+        load_b(KS - 1, nx);
         __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -400,8 +400,9 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 
 static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
-size_t mfma_fwd_workspace(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, BK) * 2); }
-size_t mfma_bwd_input_workspace(int64_t N, int64_t K) { return (size_t)(round_up(K, 32) * round_up(N, BK) * 2); }
+constexpr int RPAD = 128;  // contraction padding of the expanded operand: the longest K-step of any tile configuration
+size_t mfma_fwd_workspace(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, RPAD) * 2); }
+size_t mfma_bwd_input_workspace(int64_t N, int64_t K) { return (size_t)(round_up(K, 32) * round_up(N, RPAD) * 2); }
 
 template <int TM, int TN>
 static hipError_t launch_gemm_cfg(const bf16_t* A, int64_t lda, const u32x4* frag, bf16_t* C, int64_t ldc, int64_t M,
@@ -433,7 +434,7 @@ static hipError_t launch_gemm(const bf16_t* A, int64_t lda, const u32x4* frag, b
 
 hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
                            int64_t K, int q, void* y, void* workspace, hipStream_t st) {
-    const int64_t R16 = round_up(K, BK) / 16;
+    const int64_t R16 = round_up(K, RPAD) / 16;
     const int64_t ct = (N + 31) / 32;
     dim3 grid((unsigned)ct, (unsigned)((R16 / 2 + 7) / 8));
     hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16, (u32x4*)workspace);
@@ -444,7 +445,7 @@ hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const voi
 
 hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_t, const float* alpha, const void* dy,
                                  int64_t T, int64_t N, int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
-    const int64_t R16 = round_up(N, BK) / 16;
+    const int64_t R16 = round_up(N, RPAD) / 16;
     dim3 grid((unsigned)(K / 32), (unsigned)((R16 / 2 + 7) / 8));
     if (packed_t && N % 32 == 0)
         hipLaunchKernelGGL(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, q, R16,
