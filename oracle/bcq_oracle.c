@@ -253,3 +253,102 @@ void orc_bwd_alpha_rows(const int8_t* planes, const float* x, const float* dy, i
             out[(int64_t)i * cnt + j] = grad_scale * g;
         }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Group-wise scales (Appendix C "group-wise quantization"; Table 1 rows with g < h_in;
+ * Section 4.1, remark after Eq. 4): every row of W is cut into K/g consecutive vectors
+ * of length g and each vector has its own q scales.  Shapes: alpha[q][N][K/g],
+ * planes[q][N][K] as before.  g must divide K.  The functions below are the definitions
+ * above with alpha_i[n] replaced by alpha_i[n][k / g]; g = K gives the row-wise case.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Greedy BCQ of every length-g vector on its own (Eq. ap1-ap3 applied per vector). */
+void orc_quantize_g(const float* W, int64_t N, int64_t K, int64_t g, int q, float* alpha,
+                    int8_t* planes, double* margin) {
+    int64_t G = K / g;
+#pragma omp parallel
+    {
+        double* r = (double*)malloc(sizeof(double) * (size_t)g);
+        float a[64];
+        double m[64];
+#pragma omp for schedule(static)
+        for (int64_t v = 0; v < N * G; ++v) { /* v = n * G + group: vectors are consecutive in memory */
+            greedy_row(W + v * g, g, q, NULL, NULL, a, planes + v * g, N * K, m, r);
+            for (int i = 0; i < q; ++i) {
+                alpha[(int64_t)i * N * G + v] = a[i];
+                if (margin) margin[(int64_t)i * N * G + v] = m[i];
+            }
+        }
+        free(r);
+    }
+}
+
+/* Eq. 1 per vector: What[n][k] = sum_i alpha_i[n][k/g] * B_i[n][k]. */
+static double what_g(const float* alpha, const int8_t* planes, int64_t N, int64_t K, int64_t g,
+                     int q, int64_t n, int64_t k) {
+    int64_t G = K / g;
+    double s = 0.0;
+    for (int i = 0; i < q; ++i)
+        s += (double)alpha[((int64_t)i * N + n) * G + k / g] * (double)planes[((int64_t)i * N + n) * K + k];
+    return s;
+}
+
+void orc_dequant_g(const float* alpha, const int8_t* planes, int64_t N, int64_t K, int64_t g, int q,
+                   double* What) {
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) What[n * K + k] = what_g(alpha, planes, N, K, g, q, n, k);
+}
+
+/* Eq. 2 with group-wise scales, on listed entries: out[j] = y[tt[j]][nn[j]];
+ * tt == NULL means all entries in row-major order (cnt = T * N). */
+void orc_fwd_g_at(const float* alpha, const int8_t* planes, const float* x, int64_t T, int64_t N,
+                  int64_t K, int64_t g, int q, const int64_t* tt, const int64_t* nn, int64_t cnt,
+                  double* out) {
+    (void)T;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < cnt; ++j) {
+        int64_t t = tt ? tt[j] : j / N, n = tt ? nn[j] : j % N;
+        double s = 0.0;
+        for (int64_t k = 0; k < K; ++k) s += (double)x[t * K + k] * what_g(alpha, planes, N, K, g, q, n, k);
+        out[j] = s;
+    }
+}
+
+/* Eq. 3 with group-wise scales, on listed entries (tt == NULL: all, cnt = T * K). */
+void orc_bwd_input_g_at(const float* alpha, const int8_t* planes, const float* dy, int64_t T,
+                        int64_t N, int64_t K, int64_t g, int q, const int64_t* tt, const int64_t* kk,
+                        int64_t cnt, double* out) {
+    (void)T;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < cnt; ++j) {
+        int64_t t = tt ? tt[j] : j / K, k = tt ? kk[j] : j % K;
+        double s = 0.0;
+        for (int64_t n = 0; n < N; ++n) s += (double)dy[t * N + n] * what_g(alpha, planes, N, K, g, q, n, k);
+        out[j] = s;
+    }
+}
+
+/* Eq. 4 as the gradient of Eq. 2 with group-wise scales, on listed rows (rows == NULL: all N):
+ * out[i][j][c] = s * sum_t dy[t][n_j] * sum_{k in group c} B_i[n_j][k] x[t][k]. */
+void orc_bwd_alpha_g_rows(const int8_t* planes, const float* x, const float* dy, int64_t T, int64_t N,
+                          int64_t K, int64_t g, int q, int q_train, double grad_scale,
+                          const int64_t* rows, int64_t cnt, double* out) {
+    (void)q;
+    int64_t G = K / g;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int i = 0; i < q_train; ++i)
+        for (int64_t j = 0; j < cnt; ++j) {
+            int64_t n = rows ? rows[j] : j;
+            const int8_t* b = planes + ((int64_t)i * N + n) * K;
+            for (int64_t c = 0; c < G; ++c) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < T; ++t) {
+                    double p = 0.0;
+                    for (int64_t k = c * g; k < (c + 1) * g; ++k) p += (double)b[k] * (double)x[t * K + k];
+                    acc += (double)dy[t * N + n] * p;
+                }
+                out[((int64_t)i * cnt + j) * G + c] = grad_scale * acc;
+            }
+        }
+}

@@ -3,7 +3,8 @@
 TEST INFRASTRUCTURE ONLY.  Tests, the smoke check and the benchmark's
 cpu_baseline leg import this module; the GPU package never does, and this module
 imports nothing from it.  All arithmetic lives in bcq_oracle.c (fp64, naive
-loops, AlphaTuning Section 3 Eq. 1-2, Section 4.1 Eq. 3-4, Appendix C Eq. ap1-ap3);
+loops, AlphaTuning Section 3 Eq. 1-2, Section 4.1 Eq. 3-4, Appendix C Eq. ap1-ap3 and its
+group-wise paragraph);
 this file only marshals numpy arrays and builds the shared object with gcc when
 it is missing or older than its source.
 """
@@ -59,10 +60,26 @@ def num_threads():
     return int(_load().orc_num_threads())
 
 
-def quantize(W, q, with_margin=False):
-    """Greedy BCQ (Appendix C).  W[N,K] fp32 -> alpha[q,N] fp32, planes[q,N,K] int8 (+-1)."""
+def _group(K, g):
+    """Group size along K (Table 1 column g): None or K = row-wise; else g must divide K."""
+    g = K if g is None else int(g)
+    assert 1 <= g <= K and K % g == 0
+    return g
+
+
+def quantize(W, q, with_margin=False, g=None):
+    """Greedy BCQ (Appendix C).  W[N,K] fp32 -> alpha[q,N] fp32, planes[q,N,K] int8 (+-1).
+    With g < K (group-wise paragraph of Appendix C): alpha[q,N,K/g]."""
     W = _f32(W)
     N, K = W.shape
+    g = _group(K, g)
+    if g != K:
+        alpha = np.empty((q, N, K // g), np.float32)
+        planes = np.empty((q, N, K), np.int8)
+        margin = np.empty((q, N, K // g), np.float64) if with_margin else None
+        _load().orc_quantize_g(_p(W), _I64(N), _I64(K), _I64(g), _INT(q), _p(alpha), _p(planes),
+                               _p(margin) if with_margin else None)
+        return (alpha, planes, margin) if with_margin else (alpha, planes)
     alpha = np.empty((q, N), np.float32)
     planes = np.empty((q, N, K), np.int8)
     margin = np.empty((q, N), np.float64) if with_margin else None
@@ -101,12 +118,23 @@ def unpack(packed, K):
     return planes
 
 
+def _grouped(alpha, K):
+    """Group size implied by the shape of alpha: [q,N] -> K (row-wise), [q,N,G] -> K/G."""
+    if alpha.ndim == 2:
+        return K
+    assert alpha.ndim == 3 and K % alpha.shape[2] == 0
+    return K // alpha.shape[2]
+
+
 def dequant(alpha, planes):
-    """Eq. 1: What = sum_i diag(alpha_i) B_i in fp64."""
+    """Eq. 1: What = sum_i diag(alpha_i) B_i in fp64 (alpha[q,N], or alpha[q,N,K/g] group-wise)."""
     alpha = _f32(alpha)
     planes = np.ascontiguousarray(planes, dtype=np.int8)
     q, N, K = planes.shape
     What = np.empty((N, K), np.float64)
+    if alpha.ndim == 3:
+        _load().orc_dequant_g(_p(alpha), _p(planes), _I64(N), _I64(K), _I64(_grouped(alpha, K)), _INT(q), _p(What))
+        return What
     _load().orc_dequant(_p(alpha), _p(planes), _I64(N), _I64(K), _INT(q), _p(What))
     return What
 
@@ -117,8 +145,12 @@ def fwd(alpha, planes, x):
     planes = np.ascontiguousarray(planes, dtype=np.int8)
     q, N, K = planes.shape
     T = x.shape[0]
-    assert x.shape == (T, K) and alpha.shape == (q, N)
+    assert x.shape == (T, K) and alpha.shape[:2] == (q, N)
     y = np.empty((T, N), np.float64)
+    if alpha.ndim == 3:
+        _load().orc_fwd_g_at(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _I64(_grouped(alpha, K)),
+                             _INT(q), None, None, _I64(T * N), _p(y))
+        return y
     _load().orc_fwd(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _INT(q), _p(y))
     return y
 
@@ -130,6 +162,10 @@ def fwd_at(alpha, planes, x, tt, nn):
     T = x.shape[0]
     tt, nn = _i64(tt), _i64(nn)
     out = np.empty((tt.shape[0],), np.float64)
+    if alpha.ndim == 3:
+        _load().orc_fwd_g_at(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _I64(_grouped(alpha, K)),
+                             _INT(q), _p(tt), _p(nn), _I64(tt.shape[0]), _p(out))
+        return out
     _load().orc_fwd_at(_p(alpha), _p(planes), _p(x), _I64(T), _I64(N), _I64(K), _INT(q),
                        _p(tt), _p(nn), _I64(tt.shape[0]), _p(out))
     return out
@@ -143,6 +179,10 @@ def bwd_input(alpha, planes, dy):
     T = dy.shape[0]
     assert dy.shape == (T, N)
     dx = np.empty((T, K), np.float64)
+    if alpha.ndim == 3:
+        _load().orc_bwd_input_g_at(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K),
+                                   _I64(_grouped(alpha, K)), _INT(q), None, None, _I64(T * K), _p(dx))
+        return dx
     _load().orc_bwd_input(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _p(dx))
     return dx
 
@@ -154,32 +194,48 @@ def bwd_input_at(alpha, planes, dy, tt, kk):
     T = dy.shape[0]
     tt, kk = _i64(tt), _i64(kk)
     out = np.empty((tt.shape[0],), np.float64)
+    if alpha.ndim == 3:
+        _load().orc_bwd_input_g_at(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K),
+                                   _I64(_grouped(alpha, K)), _INT(q), _p(tt), _p(kk), _I64(tt.shape[0]), _p(out))
+        return out
     _load().orc_bwd_input_at(_p(alpha), _p(planes), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q),
                              _p(tt), _p(kk), _I64(tt.shape[0]), _p(out))
     return out
 
 
-def bwd_alpha(planes, x, dy, q_train=None, grad_scale=1.0):
-    """Eq. 4 read as the gradient of Eq. 2: dalpha[q_train,N] fp64."""
+def bwd_alpha(planes, x, dy, q_train=None, grad_scale=1.0, g=None):
+    """Eq. 4 read as the gradient of Eq. 2: dalpha[q_train,N] fp64; with g < K: dalpha[q_train,N,K/g]."""
     x, dy = _f32(x), _f32(dy)
     planes = np.ascontiguousarray(planes, dtype=np.int8)
     q, N, K = planes.shape
     T = x.shape[0]
     q_train = q if q_train is None else q_train
     assert x.shape == (T, K) and dy.shape == (T, N) and 1 <= q_train <= q
+    g = _group(K, g)
+    if g != K:
+        out = np.empty((q_train, N, K // g), np.float64)
+        _load().orc_bwd_alpha_g_rows(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _I64(g), _INT(q),
+                                     _INT(q_train), _DBL(grad_scale), None, _I64(N), _p(out))
+        return out
     out = np.empty((q_train, N), np.float64)
     _load().orc_bwd_alpha(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _INT(q_train),
                           _DBL(grad_scale), _p(out))
     return out
 
 
-def bwd_alpha_rows(planes, x, dy, rows, q_train=None, grad_scale=1.0):
+def bwd_alpha_rows(planes, x, dy, rows, q_train=None, grad_scale=1.0, g=None):
     x, dy = _f32(x), _f32(dy)
     planes = np.ascontiguousarray(planes, dtype=np.int8)
     q, N, K = planes.shape
     T = x.shape[0]
     q_train = q if q_train is None else q_train
     rows = _i64(rows)
+    g = _group(K, g)
+    if g != K:
+        out = np.empty((q_train, rows.shape[0], K // g), np.float64)
+        _load().orc_bwd_alpha_g_rows(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _I64(g), _INT(q),
+                                     _INT(q_train), _DBL(grad_scale), _p(rows), _I64(rows.shape[0]), _p(out))
+        return out
     out = np.empty((q_train, rows.shape[0]), np.float64)
     _load().orc_bwd_alpha_rows(_p(planes), _p(x), _p(dy), _I64(T), _I64(N), _I64(K), _INT(q), _INT(q_train),
                                _DBL(grad_scale), _p(rows), _I64(rows.shape[0]), _p(out))

@@ -334,3 +334,115 @@ def test_bwd_alpha_scale_and_subset(oracle):
     assert first.shape == (1, N) and np.array_equal(first[0], full[0])
     rows = np.array([11, 0, 5])
     assert np.array_equal(oracle.bwd_alpha_rows(planes, x, dy, rows), full[:, rows])
+
+
+# ---------------------------------------------------------------- group-wise scales (Appendix C, Table 1, Table 4)
+
+def _rep(alpha, g):
+    """alpha[q,N,G] -> [q,N,K] fp64 with every scale repeated over its g columns (numpy, independent of the oracle)."""
+    return np.repeat(alpha.astype(np.float64), g, axis=2)
+
+
+def test_groupwise_table4_trainable_parameters(oracle):
+    """Table 4: alpha_1 count of GPT-2 medium per group size = sizes of alpha[0] the oracle's quantizer returns."""
+    h, layers = 1024, 24
+    checked = 0
+    for line in open(os.path.join(GOLDEN, "table4_groupsize.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        gs, printed, usable = line.split()
+        if usable != "1":
+            continue
+        count = 0
+        for kind in synth.LAYER_KINDS:
+            N, K = synth.layer_shape(h, kind)
+            g = K if gs == "hin" else int(gs)
+            alpha, _ = oracle.quantize(np.zeros((N, K), np.float32), 1, g=g)
+            assert alpha.shape == ((1, N) if g == K else (1, N, K // g))
+            count += alpha[0].size
+        assert abs(count * layers / 1e6 - float(printed)) < 0.0051
+        checked += 1
+    assert checked == 5
+
+
+@pytest.mark.parametrize("q,N,K,g", [(1, 7, 128, 32), (3, 5, 192, 64), (4, 9, 256, 128), (2, 3, 96, 96)])
+def test_groupwise_quantize_is_vectorwise_greedy(oracle, q, N, K, g):
+    """Appendix C, group-wise paragraph: each length-g piece of a row is quantized as a vector of its own, i.e.
+    the row-wise quantizer applied to W viewed as [N*K/g, g]; q = 1 also has the closed form of Eq. ap1."""
+    W = (_rng(50 + g).standard_normal((N, K)) * 0.02).astype(np.float32)
+    alpha, planes, margin = oracle.quantize(W, q, with_margin=True, g=g)
+    G = K // g
+    if g == K:
+        assert alpha.shape == (q, N)
+        alpha = alpha[:, :, None]
+    a_ref, b_ref = oracle.quantize(W.reshape(N * G, g), q)
+    assert np.array_equal(alpha.reshape(q, N * G), a_ref)
+    assert np.array_equal(planes.reshape(q, N * G, g), b_ref)
+    m1 = np.abs(W.astype(np.float64)).reshape(N, G, g).mean(axis=2)
+    assert np.array_equal(alpha[0], m1.astype(np.float32))
+    assert np.array_equal(planes[0], np.where(W >= 0, 1, -1))
+    # residual recurrence of Eq. ap2 / ap3 inside every group, rebuilt with numpy
+    r = W.astype(np.float64)
+    for i in range(q):
+        assert np.array_equal(planes[i], np.where(r >= 0, 1, -1))
+        assert np.allclose(alpha[i], np.abs(r).reshape(N, G, g).mean(axis=2), rtol=1e-6)
+        r = r - _rep(alpha[i:i + 1], g)[0] * planes[i]
+
+
+def test_groupwise_dequant_fwd_bwd_input_reduce_to_matmul(oracle):
+    """Eq. 1-3 with alpha_i[n][k/g]: dequant equals the repeated-scale sum; forward and input gradient equal
+    numpy matmuls with that matrix; the sampled variants return the same entries."""
+    T, N, K, q, g = 6, 10, 192, 3, 64
+    rng = _rng(61)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    alpha = rng.uniform(0.01, 1.0, size=(q, N, K // g)).astype(np.float32)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    dy = rng.standard_normal((T, N)).astype(np.float32)
+    What = (_rep(alpha, g) * planes).sum(axis=0)
+    assert np.allclose(oracle.dequant(alpha, planes), What, rtol=1e-14, atol=1e-15)
+    y = oracle.fwd(alpha, planes, x)
+    dx = oracle.bwd_input(alpha, planes, dy)
+    assert np.allclose(y, x.astype(np.float64) @ What.T, rtol=1e-12, atol=1e-13)
+    assert np.allclose(dx, dy.astype(np.float64) @ What, rtol=1e-12, atol=1e-13)
+    tt, nn, kk = rng.integers(0, T, 40), rng.integers(0, N, 40), rng.integers(0, K, 40)
+    assert np.array_equal(oracle.fwd_at(alpha, planes, x, tt, nn), y[tt, nn])
+    assert np.array_equal(oracle.bwd_input_at(alpha, planes, dy, tt, kk), dx[tt, kk])
+    # scales that differ between groups must matter: swapping two groups' scales changes the result
+    swapped = alpha.copy()
+    swapped[:, :, [0, 1]] = swapped[:, :, [1, 0]]
+    assert not np.allclose(oracle.fwd(swapped, planes, x), y)
+    # equal scales in every group = the row-wise layer
+    same = np.repeat(alpha[:, :, :1], K // g, axis=2)
+    assert np.allclose(oracle.fwd(same, planes, x), oracle.fwd(same[:, :, 0], planes, x), rtol=1e-13, atol=1e-14)
+
+
+def test_groupwise_bwd_alpha_crossform_fd_additivity(oracle):
+    """Eq. 4 per group: dalpha_i[n][c] = sum_{k in c} B_i[n,k] (dY^T X)[n,k]; finite differences of <dy, fwd>
+    in single scales; the groups of a row add up to the row-wise gradient; scale, subset and row variants."""
+    T, N, K, q, g = 7, 11, 256, 3, 64
+    rng = _rng(62)
+    planes = rng.choice(np.array([-1, 1], np.int8), size=(q, N, K))
+    alpha = rng.uniform(0.01, 1.0, size=(q, N, K // g)).astype(np.float32)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    dy = rng.standard_normal((T, N)).astype(np.float32)
+    da = oracle.bwd_alpha(planes, x, dy, g=g)
+    assert da.shape == (q, N, K // g)
+    Gm = dy.astype(np.float64).T @ x.astype(np.float64)
+    ref = (planes.astype(np.float64) * Gm[None]).reshape(q, N, K // g, g).sum(axis=3)
+    assert np.allclose(da, ref, rtol=1e-11, atol=1e-13)
+    assert np.allclose(da.sum(axis=2), oracle.bwd_alpha(planes, x, dy), rtol=1e-11, atol=1e-12)
+    y = oracle.fwd(alpha, planes, x)
+    assert float((dy * y).sum()) == pytest.approx(float((alpha.astype(np.float64) * da).sum()), rel=1e-11)
+    for (i, n, c) in [(0, 0, 0), (1, 7, 3), (2, 10, 2)]:
+        ap, am = alpha.copy(), alpha.copy()
+        h = np.float32(2.0 ** -6)
+        ap[i, n, c] += h
+        am[i, n, c] -= h
+        step = float(ap[i, n, c]) - float(am[i, n, c])
+        fd = float((dy * (oracle.fwd(ap, planes, x) - oracle.fwd(am, planes, x))).sum()) / step
+        assert fd == pytest.approx(da[i, n, c], rel=1e-9, abs=1e-12)
+    assert np.allclose(oracle.bwd_alpha(planes, x, dy, grad_scale=1.0 / g, g=g), da / g, rtol=1e-15)
+    first = oracle.bwd_alpha(planes, x, dy, q_train=1, g=g)
+    assert first.shape == (1, N, K // g) and np.array_equal(first[0], da[0])
+    rows = np.array([10, 0, 4])
+    assert np.array_equal(oracle.bwd_alpha_rows(planes, x, dy, rows, g=g), da[:, rows])
