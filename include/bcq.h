@@ -13,6 +13,12 @@
  * Transposed twin (optional accelerator for the input gradient): packed_t[i][k][v], v < N/32;
  * bit j of word v is the sign of B_i[32v + j][k].  It holds the same information as `packed`.
  *
+ * Group-wise scales (Appendix C, paragraph "group-wise quantization"; Table 1 rows with g < h_in; Section 4.1,
+ * remark after Eq. 4): every row is cut into K/g consecutive vectors of length g, each with its own q scales:
+ *     What[n][k] = sum_i alpha_i[n][k / g] * B_i[n][k],   alpha[q][N][K/g] fp32.
+ * The *_grouped entry points take g (32 <= g <= K, g % 32 == 0, K % g == 0, else BCQ_ERR_SHAPE); with g = K they
+ * are the row-wise calls, which forward to them.  The sign planes and their packed layouts do not depend on g.
+ *
  * General rules for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library never allocates,
  *     frees or keeps them.  Arrays are dense row-major with the innermost extent as stride.
@@ -45,7 +51,8 @@ typedef enum {
     BCQ_OK = 0,
     BCQ_ERR_NULL = 1,      /* a required pointer is NULL                                        */
     BCQ_ERR_SHAPE = 2,     /* N,K,T < 1; q outside [1,8]; K % 32 != 0; q_train outside [1,q];
-                              N % 32 != 0 with a transposed twin; K above the quantizer's limit */
+                              N % 32 != 0 with a transposed twin; K above the quantizer's limit;
+                              g outside [32,K], g % 32 != 0 or K % g != 0                       */
     BCQ_ERR_DTYPE = 3,     /* dtype is neither BCQ_F32 nor BCQ_BF16, or op code unknown         */
     BCQ_ERR_ALIGN = 4,     /* a data pointer or the workspace is not 16-byte aligned            */
     BCQ_ERR_WORKSPACE = 5, /* workspace non-NULL but smaller than bcq_workspace_bytes()         */
@@ -68,12 +75,16 @@ typedef enum {
 /* Static, NUL-terminated description of a status code. */
 const char* bcq_status_string(bcq_status s);
 
-/* ABI version, bumped on any signature change. */
+/* ABI version, bumped on any signature change or addition (2: *_grouped entry points). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
  * T is ignored for BCQ_OP_QUANTIZE.  Host-only: touches no device. */
 bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, int dtype, size_t* out);
+
+/* bcq_workspace_bytes for group size g. */
+bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
+                                       size_t* out);
 
 /* Greedy BCQ quantizer (Appendix C: Eq. ap1 for the first plane, Eq. ap2-ap3 for the others).
  * Per row n: r = W[n][:] in fp64; for i = 0..q-1: B_i = (r >= 0 ? +1 : -1) (so sign(0) = +1),
@@ -87,6 +98,13 @@ bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, i
  * K <= BCQ_QUANTIZE_MAX_K, else BCQ_ERR_SHAPE. */
 bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                         int8_t* planes_i8, void* workspace, size_t workspace_bytes, void* stream);
+
+/* bcq_quantize on every length-g vector of every row on its own (Appendix C, group-wise paragraph):
+ * alpha [q][N][K/g] out; packed and planes_i8 as above.  g <= BCQ_QUANTIZE_MAX_K and N*K/g < 2^31, else
+ * BCQ_ERR_SHAPE.  The status word counts vectors (not rows) that hold a NaN or Inf. */
+bcq_status bcq_quantize_grouped(const float* W, int64_t N, int64_t K, int64_t g, int q, float* alpha,
+                                uint32_t* packed, int8_t* planes_i8, void* workspace, size_t workspace_bytes,
+                                void* stream);
 
 /* Bit-plane pack (Table 1 gives the index order B:(q, h_out, h_in); footnote of Section 3: contiguous rows).
  *   planes_i8 [q][N][K] int8, in.  Only the sign of each byte is read: v >= 0 -> bit 1 (+1), v < 0 -> bit 0.
@@ -109,6 +127,11 @@ bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void
                           int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
                           void* stream);
 
+/* Eq. 2 with group-wise scales alpha [q][N][K/g]: y[t][n] = sum_k x[t][k] * sum_i alpha_i[n][k/g] * B_i[n][k]. */
+bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                                  int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
 /* Input gradient (Eq. 3): dx[t][k] = sum_n dy[t][n] * sum_i alpha_i[n] * B_i[n][k].
  *   packed [q][N][K/32] in; packed_t [q][K][N/32] in, may be NULL (non-NULL needs N % 32 == 0); alpha [q][N] in;
  *   dy [T][N] `dtype` in; dx [T][K] `dtype` out.
@@ -117,6 +140,11 @@ bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void
 bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
                                 const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 3 with group-wise scales alpha [q][N][K/g]; arguments as bcq_linear_bwd_input. */
+bcq_status bcq_linear_bwd_input_grouped(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
+                                        const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int64_t g,
+                                        int q, void* dx, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Scale gradient (Eq. 4, read as the gradient of Eq. 2 with the empirical 1/g_L left to the caller):
  *   dalpha[i][n] = grad_scale * sum_t dy[t][n] * sum_k B_i[n][k] * x[t][k]   for i < q_train.
@@ -127,6 +155,12 @@ bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t
 bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                 int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 4 per scale group: dalpha[i][n][c] = grad_scale * sum_t dy[t][n] * sum_{k in group c} B_i[n][k] * x[t][k],
+ * dalpha [q_train][N][K/g] fp32 out, OVERWRITTEN.  The paper's damping is grad_scale = 1/g. */
+bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                        int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                        float* dalpha, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,9 @@ OP_QUANTIZE, OP_FWD, OP_BWD_INPUT, OP_BWD_ALPHA = 0, 1, 2, 3
 QUANTIZE_MAX_K = 16384
 
 EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_quantize", "bcq_pack",
-           "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha")
+           "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha",
+           "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
+           "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped")
 
 _lib = None
 
@@ -50,6 +52,11 @@ def load():
     lib.bcq_linear_fwd.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_bwd_input.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_bwd_alpha.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, i32, f32, vp, vp, sz, vp]
+    lib.bcq_workspace_bytes_grouped.argtypes = [i32, i64, i64, i64, i64, i32, i32, ctypes.POINTER(sz)]
+    lib.bcq_quantize_grouped.argtypes = [vp, i64, i64, i64, i32, vp, vp, vp, vp, sz, vp]
+    lib.bcq_linear_fwd_grouped.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.bcq_linear_bwd_input_grouped.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.bcq_linear_bwd_alpha_grouped.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, i32, f32, vp, vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -69,6 +76,14 @@ def workspace_bytes(op, T, N, K, q, dtype):
     st = load().bcq_workspace_bytes(op, T, N, K, q, dtype, ctypes.byref(out))
     if st:
         raise BcqError(st, "bcq_workspace_bytes")
+    return int(out.value)
+
+
+def workspace_bytes_grouped(op, T, N, K, g, q, dtype):
+    out = ctypes.c_size_t(0)
+    st = load().bcq_workspace_bytes_grouped(op, T, N, K, g, q, dtype, ctypes.byref(out))
+    if st:
+        raise BcqError(st, "bcq_workspace_bytes_grouped")
     return int(out.value)
 
 
@@ -203,4 +218,83 @@ def bcq_linear_bwd_alpha(packed, x, dy, q_train=None, grad_scale=1.0, dalpha=Non
     wp, wb = _ws(workspace)
     _check(load().bcq_linear_bwd_alpha(_ptr(packed), _ptr(x), _ptr(dy), dt, T, N, K, q, q_train,
                                        float(grad_scale), _ptr(dalpha), wp, wb, _stream()), "bcq_linear_bwd_alpha")
+    return dalpha
+
+
+# ---- group-wise scales: alpha[q, N, K/g] (g = K gives the row-wise calls above) ----------------------------
+
+def bcq_quantize_grouped(W, q, g, alpha=None, packed=None, planes_i8=None, want_planes=False, workspace=None):
+    """Greedy BCQ of every length-g vector of W[N,K] -> (alpha[q,N,K/g] f32, packed[q,N,K/32], planes_i8 or None)."""
+    N, K = W.shape
+    g = int(g)
+    G = K // max(g, 1)
+    _need(W, torch.float32, (N, K), "W")
+    dev = W.device
+    alpha = torch.empty((q, N, G), dtype=torch.float32, device=dev) if alpha is None else alpha
+    packed = torch.empty((q, N, K // 32), dtype=torch.int32, device=dev) if packed is None else packed
+    if planes_i8 is None and want_planes:
+        planes_i8 = torch.empty((q, N, K), dtype=torch.int8, device=dev)
+    _need(alpha, torch.float32, (q, N, G), "alpha")
+    _need(packed, torch.int32, (q, N, K // 32), "packed")
+    if planes_i8 is not None:
+        _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_quantize_grouped(_ptr(W), N, K, g, q, _ptr(alpha), _ptr(packed), _ptr(planes_i8), wp, wb,
+                                       _stream()), "bcq_quantize_grouped")
+    return alpha, packed, planes_i8
+
+
+def bcq_linear_fwd_grouped(packed, alpha, x, g, y=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    g = int(g)
+    dt = _act_dtype(x)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N, K // max(g, 1)), "alpha")
+    _need(x, x.dtype, (T, K), "x")
+    y = torch.empty((T, N), dtype=x.dtype, device=x.device) if y is None else y
+    _need(y, x.dtype, (T, N), "y")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_fwd_grouped(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, g, q, _ptr(y), wp, wb,
+                                         _stream()), "bcq_linear_fwd_grouped")
+    return y
+
+
+def bcq_linear_bwd_input_grouped(packed, alpha, dy, g, packed_t=None, dx=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = dy.shape[0]
+    g = int(g)
+    dt = _act_dtype(dy)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N, K // max(g, 1)), "alpha")
+    _need(dy, dy.dtype, (T, N), "dy")
+    if packed_t is not None:
+        _need(packed_t, torch.int32, (q, K, N // 32), "packed_t")
+    dx = torch.empty((T, K), dtype=dy.dtype, device=dy.device) if dx is None else dx
+    _need(dx, dy.dtype, (T, K), "dx")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_bwd_input_grouped(_ptr(packed), _ptr(packed_t), _ptr(alpha), _ptr(dy), dt, T, N, K, g,
+                                               q, _ptr(dx), wp, wb, _stream()), "bcq_linear_bwd_input_grouped")
+    return dx
+
+
+def bcq_linear_bwd_alpha_grouped(packed, x, dy, g, q_train=None, grad_scale=1.0, dalpha=None, workspace=None):
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    g = int(g)
+    dt = _act_dtype(x)
+    q_train = q if q_train is None else int(q_train)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(x, x.dtype, (T, K), "x")
+    _need(dy, x.dtype, (T, N), "dy")
+    G = K // max(g, 1)
+    dalpha = torch.empty((q_train, N, G), dtype=torch.float32, device=x.device) if dalpha is None else dalpha
+    _need(dalpha, torch.float32, (q_train, N, G), "dalpha")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_bwd_alpha_grouped(_ptr(packed), _ptr(x), _ptr(dy), dt, T, N, K, g, q, q_train,
+                                               float(grad_scale), _ptr(dalpha), wp, wb, _stream()),
+           "bcq_linear_bwd_alpha_grouped")
     return dalpha

@@ -21,6 +21,12 @@ bcq_status check_shape(int64_t T, int64_t N, int64_t K, int q) {
     return BCQ_OK;
 }
 
+// Group size along K: a multiple of 32 (a packed word never straddles two groups) that divides K.
+bcq_status check_group(int64_t K, int64_t g) {
+    if (g < 32 || g > K || g % 32 != 0 || K % g != 0) return BCQ_ERR_SHAPE;
+    return BCQ_OK;
+}
+
 // One capability probe per device, cached: 1 = gfx950, 0 = anything else.
 bcq_status check_device() {
     static int cache[64];  // 0 = unknown, 1 = ok, 2 = wrong
@@ -52,30 +58,34 @@ bcq_status check_workspace(const void* ws, size_t have, size_t need) {
 // Token count from which the tiled matrix-core kernels are used (bf16 activations, workspace given).
 constexpr int64_t kMfmaMinTokens = 32;
 
-// Small-token kernels: bf16, fewer tokens than the tiled kernels want.
-bool small_fwd_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T < kMfmaMinTokens; }
-bool small_bwd_alpha_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T <= 16; }
-bool small_bwd_input_ok(int64_t T, int64_t N, int dtype) { return dtype == BCQ_BF16 && T < kMfmaMinTokens && N % 32 == 0; }
-
-bool mfma_fwd_ok(int64_t T, int dtype) { return dtype == BCQ_BF16 && T >= kMfmaMinTokens; }
-bool mfma_bwd_input_ok(int64_t T, int64_t N, int dtype) {
-    return dtype == BCQ_BF16 && T >= kMfmaMinTokens && N % 8 == 0;  // rows of dy must be 16-byte aligned
+// Small-token kernels: bf16, fewer tokens than the tiled kernels want, row-wise scales (they apply alpha after
+// the contraction over all of K).  Group-wise scales take the tiled kernels at every token count.
+bool small_fwd_ok(int64_t T, bool rowwise, int dtype) { return dtype == BCQ_BF16 && rowwise && T < kMfmaMinTokens; }
+bool small_bwd_alpha_ok(int64_t T, bool rowwise, int dtype) { return dtype == BCQ_BF16 && rowwise && T <= 16; }
+bool small_bwd_input_ok(int64_t T, int64_t N, bool rowwise, int dtype) {
+    return dtype == BCQ_BF16 && rowwise && T < kMfmaMinTokens && N % 32 == 0;
 }
 
-bool mfma_bwd_alpha_ok(int64_t T, int64_t N, int64_t K, int dtype) {
-    (void)K;
-    return dtype == BCQ_BF16 && T >= 64 && N % 8 == 0 && N >= 8 && K >= 8;  // rows of dy 16-byte aligned
+bool mfma_fwd_ok(int64_t T, bool rowwise, int dtype) {
+    return dtype == BCQ_BF16 && (T >= kMfmaMinTokens || !rowwise);
+}
+bool mfma_bwd_input_ok(int64_t T, int64_t N, bool rowwise, int dtype) {
+    return dtype == BCQ_BF16 && (T >= kMfmaMinTokens || !rowwise) && N % 8 == 0;  // rows of dy 16-byte aligned
+}
+bool mfma_bwd_alpha_ok(int64_t T, int64_t N, int64_t K, bool rowwise, int dtype) {
+    return dtype == BCQ_BF16 && (T > 16 || !rowwise) && N % 8 == 0 && N >= 8 && K >= 8;  // rows of dy 16-byte aligned
 }
 
-size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int q, int dtype) {
-    (void)q;
+size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype) {
+    const bool rowwise = (g == K);
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
-        case BCQ_OP_FWD: return mfma_fwd_ok(T, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
+        case BCQ_OP_FWD: return mfma_fwd_ok(T, rowwise, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
         case BCQ_OP_BWD_INPUT:
-            if (small_bwd_input_ok(T, N, dtype)) return bcq::small_bwd_input_workspace(T, N, q);
-            return mfma_bwd_input_ok(T, N, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
-        case BCQ_OP_BWD_ALPHA: return mfma_bwd_alpha_ok(T, N, K, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, q) : 0;
+            if (small_bwd_input_ok(T, N, rowwise, dtype)) return bcq::small_bwd_input_workspace(T, N, q);
+            return mfma_bwd_input_ok(T, N, rowwise, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
+        case BCQ_OP_BWD_ALPHA:
+            return mfma_bwd_alpha_ok(T, N, K, rowwise, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, g, q) : 0;
         default: return 0;
     }
 }
@@ -98,31 +108,50 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 1; }
+int bcq_abi_version(void) { return 2; }
 
-bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, int dtype, size_t* out) {
+bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
+                                       size_t* out) {
     if (!out) return BCQ_ERR_NULL;
     if (op < BCQ_OP_QUANTIZE || op > BCQ_OP_BWD_ALPHA) return BCQ_ERR_DTYPE;
     if (op == BCQ_OP_QUANTIZE) T = 1;
     bcq_status s = check_shape(T, N, K, q);
     if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
     if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
-    *out = workspace_need(op, T, N, K, q, dtype);
+    *out = workspace_need(op, T, N, K, g, q, dtype);
     return BCQ_OK;
+}
+
+bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, int dtype, size_t* out) {
+    return bcq_workspace_bytes_grouped(op, T, N, K, K, q, dtype, out);
+}
+
+bcq_status bcq_quantize_grouped(const float* W, int64_t N, int64_t K, int64_t g, int q, float* alpha,
+                                uint32_t* packed, int8_t* planes_i8, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    if (!W || !alpha || !packed) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
+    if (g > BCQ_QUANTIZE_MAX_K) return BCQ_ERR_SHAPE;
+    const int64_t vectors = N * (K / g);  // one workgroup each
+    if (vectors > 0x7FFFFFFF) return BCQ_ERR_SHAPE;
+    if (misaligned(W) || misaligned(alpha) || misaligned(packed) || misaligned(planes_i8)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_QUANTIZE, 1, N, K, g, q, BCQ_F32));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    // W[N][K] row-major is also [N K / g][g] row-major, and alpha, packed and planes_i8 keep their layouts under
+    // that view: group-wise quantization is the row-wise kernel on the reshaped matrix.
+    return done(bcq::launch_quantize(W, vectors, g, q, alpha, packed, planes_i8, (int*)workspace, (hipStream_t)stream));
 }
 
 bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                         int8_t* planes_i8, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!W || !alpha || !packed) return BCQ_ERR_NULL;
-    bcq_status s = check_shape(1, N, K, q);
-    if (s != BCQ_OK) return s;
-    if (K > BCQ_QUANTIZE_MAX_K) return BCQ_ERR_SHAPE;
-    if (misaligned(W) || misaligned(alpha) || misaligned(packed) || misaligned(planes_i8)) return BCQ_ERR_ALIGN;
-    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_QUANTIZE, 1, N, K, q, BCQ_F32));
-    if (s != BCQ_OK) return s;
-    s = check_device();
-    if (s != BCQ_OK) return s;
-    return done(bcq::launch_quantize(W, N, K, q, alpha, packed, planes_i8, (int*)workspace, (hipStream_t)stream));
+    return bcq_quantize_grouped(W, N, K, K, q, alpha, packed, planes_i8, workspace, workspace_bytes, stream);
 }
 
 bcq_status bcq_pack(const int8_t* planes_i8, int64_t N, int64_t K, int q, uint32_t* packed, void* stream) {
@@ -157,66 +186,95 @@ bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int
     return done(bcq::launch_pack_transposed(packed, N, K, q, packed_t, (hipStream_t)stream));
 }
 
-bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
-                          int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
-                          void* stream) {
+bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                                  int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
     if (!packed || !alpha || !x || !y) return BCQ_ERR_NULL;
     bcq_status s = check_shape(T, N, K, q);
     if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
     if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
     if (misaligned(packed) || misaligned(alpha) || misaligned(x) || misaligned(y)) return BCQ_ERR_ALIGN;
-    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_FWD, T, N, K, q, dtype));
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_FWD, T, N, K, g, q, dtype));
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
-    if (small_fwd_ok(T, dtype)) return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, (hipStream_t)stream));
-    if (workspace && mfma_fwd_ok(T, dtype))
-        return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, q, y, workspace, (hipStream_t)stream));
-    return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, q, y, (hipStream_t)stream));
+    const bool rowwise = (g == K);
+    hipStream_t st = (hipStream_t)stream;
+    if (small_fwd_ok(T, rowwise, dtype)) return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, st));
+    if (workspace && mfma_fwd_ok(T, rowwise, dtype))
+        return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, g, q, y, workspace, st));
+    return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, g, q, y, st));
 }
 
-bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
-                                const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
-                                void* workspace, size_t workspace_bytes, void* stream) {
+bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                          int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    return bcq_linear_fwd_grouped(packed, alpha, x, dtype, T, N, K, K, q, y, workspace, workspace_bytes, stream);
+}
+
+bcq_status bcq_linear_bwd_input_grouped(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
+                                        const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int64_t g,
+                                        int q, void* dx, void* workspace, size_t workspace_bytes, void* stream) {
     if (!packed || !alpha || !dy || !dx) return BCQ_ERR_NULL;
     bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
     if (s != BCQ_OK) return s;
     if (packed_t && N % 32 != 0) return BCQ_ERR_SHAPE;
     if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
     if (misaligned(packed) || misaligned(packed_t) || misaligned(alpha) || misaligned(dy) || misaligned(dx))
         return BCQ_ERR_ALIGN;
-    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_INPUT, T, N, K, q, dtype));
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_INPUT, T, N, K, g, q, dtype));
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
-    if (workspace && packed_t && small_bwd_input_ok(T, N, dtype))
-        return done(bcq::launch_bwd_input_small(packed_t, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
-    if (workspace && mfma_bwd_input_ok(T, N, dtype))
-        return done(bcq::launch_bwd_input_mfma(packed, packed_t, alpha, dy, T, N, K, q, dx, workspace, (hipStream_t)stream));
-    return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, q, dx, (hipStream_t)stream));
+    const bool rowwise = (g == K);
+    hipStream_t st = (hipStream_t)stream;
+    if (workspace && packed_t && small_bwd_input_ok(T, N, rowwise, dtype))
+        return done(bcq::launch_bwd_input_small(packed_t, alpha, dy, T, N, K, q, dx, workspace, st));
+    if (workspace && mfma_bwd_input_ok(T, N, rowwise, dtype))
+        return done(bcq::launch_bwd_input_mfma(packed, packed_t, alpha, dy, T, N, K, g, q, dx, workspace, st));
+    return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, g, q, dx, st));
+}
+
+bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
+                                const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    return bcq_linear_bwd_input_grouped(packed, packed_t, alpha, dy, dtype, T, N, K, K, q, dx, workspace,
+                                        workspace_bytes, stream);
+}
+
+bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                        int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                        float* dalpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!packed || !x || !dy || !dalpha) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
+    if (q_train < 1 || q_train > q) return BCQ_ERR_SHAPE;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    if (misaligned(packed) || misaligned(x) || misaligned(dy) || misaligned(dalpha)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_ALPHA, T, N, K, g, q, dtype));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    const bool rowwise = (g == K);
+    hipStream_t st = (hipStream_t)stream;
+    if (small_bwd_alpha_ok(T, rowwise, dtype))
+        return done(bcq::launch_bwd_alpha_small(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, st));
+    if (workspace && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
+        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace, st));
+    return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, g, q, q_train, grad_scale, dalpha, st));
 }
 
 bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                 int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
                                 void* workspace, size_t workspace_bytes, void* stream) {
-    if (!packed || !x || !dy || !dalpha) return BCQ_ERR_NULL;
-    bcq_status s = check_shape(T, N, K, q);
-    if (s != BCQ_OK) return s;
-    if (q_train < 1 || q_train > q) return BCQ_ERR_SHAPE;
-    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
-    if (misaligned(packed) || misaligned(x) || misaligned(dy) || misaligned(dalpha)) return BCQ_ERR_ALIGN;
-    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_ALPHA, T, N, K, q, dtype));
-    if (s != BCQ_OK) return s;
-    s = check_device();
-    if (s != BCQ_OK) return s;
-    if (small_bwd_alpha_ok(T, dtype))
-        return done(bcq::launch_bwd_alpha_small(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha,
-                                                (hipStream_t)stream));
-    if (workspace && mfma_bwd_alpha_ok(T, N, K, dtype))
-        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, workspace,
-                                               (hipStream_t)stream));
-    return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, q, q_train, grad_scale, dalpha,
-                                              (hipStream_t)stream));
+    return bcq_linear_bwd_alpha_grouped(packed, x, dy, dtype, T, N, K, K, q, q_train, grad_scale, dalpha, workspace,
+                                        workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -28,22 +28,24 @@ __device__ __forceinline__ void load32(const XT* p, float (&v)[32]) {
 template <typename XT>
 __global__ __launch_bounds__(256) void fwd_generic_kernel(const uint32_t* __restrict__ packed,
                                                           const float* __restrict__ alpha, const XT* __restrict__ x,
-                                                          XT* __restrict__ y, int64_t T, int64_t N, int64_t K, int q) {
+                                                          XT* __restrict__ y, int64_t T, int64_t N, int64_t K,
+                                                          int64_t g, int q) {
     const int lane = threadIdx.x & 63;
     const int64_t n = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
     const int64_t t0 = (int64_t)blockIdx.x * GEN_TT;
     if (n >= N) return;  // whole wave leaves together
-    const int64_t Kw = K / 32;
-    float a[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] = (i < q) ? alpha[(int64_t)i * N + n] : 0.f;
+    const int64_t Kw = K / 32, G = K / g, gw = g / 32;
     float acc[GEN_TT];
 #pragma unroll
     for (int t = 0; t < GEN_TT; ++t) acc[t] = 0.f;
     for (int64_t w = lane; w < Kw; w += 64) {
         uint32_t bits[8];
+        float a[8];  // scales of the group this word lies in (a word never straddles groups: g % 32 == 0)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bits[i] = (i < q) ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
+        for (int i = 0; i < 8; ++i) {
+            bits[i] = (i < q) ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
+            a[i] = (i < q) ? alpha[((int64_t)i * N + n) * G + w / gw] : 0.f;
+        }
 #pragma unroll
         for (int t = 0; t < GEN_TT; ++t) {
             if (t0 + t < T) {
@@ -70,34 +72,36 @@ template <typename XT>
 __global__ __launch_bounds__(256) void bwd_alpha_generic_kernel(const uint32_t* __restrict__ packed,
                                                                 const XT* __restrict__ x, const XT* __restrict__ dy,
                                                                 float* __restrict__ dalpha, int64_t T, int64_t N,
-                                                                int64_t K, int q_train, float grad_scale) {
+                                                                int64_t K, int64_t g, int q_train, float grad_scale) {
     const int lane = threadIdx.x & 63;
     const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (n >= N) return;
-    const int64_t Kw = K / 32;
-    float g[8];
+    const int64_t Kw = K / 32, G = K / g, gw = g / 32;
+    for (int64_t grp = 0; grp < G; ++grp) {  // one scale group at a time; the lanes stride over its words
+        float acc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) g[i] = 0.f;
-    for (int64_t w = lane; w < Kw; w += 64) {
-        uint32_t bits[8];
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        for (int64_t w = grp * gw + lane; w < (grp + 1) * gw; w += 64) {
+            uint32_t bits[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bits[i] = (i < q_train) ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
-        for (int64_t t = 0; t < T; ++t) {
-            float v[32];
-            load32<XT>(x + t * K + 32 * w, v);
-            const float d = Elem<XT>::load(dy + t * N + n);
+            for (int i = 0; i < 8; ++i) bits[i] = (i < q_train) ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
+            for (int64_t t = 0; t < T; ++t) {
+                float v[32];
+                load32<XT>(x + t * K + 32 * w, v);
+                const float d = Elem<XT>::load(dy + t * N + n);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (i < q_train) g[i] += d * signed_sum32(bits[i], v);
+                for (int i = 0; i < 8; ++i)
+                    if (i < q_train) acc[i] += d * signed_sum32(bits[i], v);
+            }
         }
-    }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        if (i < q_train) {
-            float s = g[i];
+        for (int i = 0; i < 8; ++i) {
+            if (i < q_train) {
+                float s = acc[i];
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-            if (lane == 0) dalpha[(int64_t)i * N + n] = grad_scale * s;
+                for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+                if (lane == 0) dalpha[((int64_t)i * N + n) * G + grp] = grad_scale * s;
+            }
         }
     }
 }
@@ -108,11 +112,11 @@ template <typename XT>
 __global__ __launch_bounds__(256) void bwd_input_generic_kernel(const uint32_t* __restrict__ packed,
                                                                 const float* __restrict__ alpha,
                                                                 const XT* __restrict__ dy, XT* __restrict__ dx,
-                                                                int64_t T, int64_t N, int64_t K, int q) {
+                                                                int64_t T, int64_t N, int64_t K, int64_t g, int q) {
     const int64_t k = (int64_t)blockIdx.y * 256 + threadIdx.x;
     const int64_t t0 = (int64_t)blockIdx.x * GEN_TT;
     if (k >= K) return;
-    const int64_t Kw = K / 32;
+    const int64_t Kw = K / 32, G = K / g, grp = k / g;
     const int64_t w = k >> 5;
     const int j = (int)(k & 31);
     float acc[GEN_TT];
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(256) void bwd_input_generic_kernel(const uint32_t* 
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             if (i < q) {
-                const float a = alpha[(int64_t)i * N + n];
+                const float a = alpha[((int64_t)i * N + n) * G + grp];
                 const uint32_t b = packed[((int64_t)i * N + n) * Kw + w];
                 what += ((b >> j) & 1u) ? a : -a;
             }
@@ -138,40 +142,40 @@ __global__ __launch_bounds__(256) void bwd_input_generic_kernel(const uint32_t* 
 }
 
 hipError_t launch_fwd_generic(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
-                              int64_t N, int64_t K, int q, void* y, hipStream_t st) {
+                              int64_t N, int64_t K, int64_t g, int q, void* y, hipStream_t st) {
     dim3 grid((unsigned)((T + GEN_TT - 1) / GEN_TT), (unsigned)((N + 3) / 4));
     if (dtype == 0)
         hipLaunchKernelGGL(fwd_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)x,
-                           (float*)y, T, N, K, q);
+                           (float*)y, T, N, K, g, q);
     else
         hipLaunchKernelGGL(fwd_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha, (const bf16_t*)x,
-                           (bf16_t*)y, T, N, K, q);
+                           (bf16_t*)y, T, N, K, g, q);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_alpha_generic(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
-                                    int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
-                                    hipStream_t st) {
+                                    int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                    float* dalpha, hipStream_t st) {
     (void)q;
     dim3 grid((unsigned)((N + 3) / 4));
     if (dtype == 0)
         hipLaunchKernelGGL(bwd_alpha_generic_kernel<float>, grid, dim3(256), 0, st, packed, (const float*)x,
-                           (const float*)dy, dalpha, T, N, K, q_train, grad_scale);
+                           (const float*)dy, dalpha, T, N, K, g, q_train, grad_scale);
     else
         hipLaunchKernelGGL(bwd_alpha_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, (const bf16_t*)x,
-                           (const bf16_t*)dy, dalpha, T, N, K, q_train, grad_scale);
+                           (const bf16_t*)dy, dalpha, T, N, K, g, q_train, grad_scale);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_input_generic(const uint32_t* packed, const float* alpha, const void* dy, int dtype,
-                                    int64_t T, int64_t N, int64_t K, int q, void* dx, hipStream_t st) {
+                                    int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, hipStream_t st) {
     dim3 grid((unsigned)((T + GEN_TT - 1) / GEN_TT), (unsigned)((K + 255) / 256));
     if (dtype == 0)
         hipLaunchKernelGGL(bwd_input_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)dy,
-                           (float*)dx, T, N, K, q);
+                           (float*)dx, T, N, K, g, q);
     else
         hipLaunchKernelGGL(bwd_input_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha,
-                           (const bf16_t*)dy, (bf16_t*)dx, T, N, K, q);
+                           (const bf16_t*)dy, (bf16_t*)dx, T, N, K, g, q);
     return hipGetLastError();
 }
 

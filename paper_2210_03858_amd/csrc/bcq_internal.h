@@ -37,26 +37,30 @@ hipError_t launch_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, 
 hipError_t launch_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                            int8_t* planes, int* status_word, hipStream_t st);
 
+// Scales are alpha[q][N][K / g] (g = group size along K, a multiple of 32 that divides K; g = K is the row-wise
+// case alpha[q][N]); the scale gradient has the same shape.
+
 // ---- any-shape kernels (plain vector ALU; need no workspace) --------------------------------
 hipError_t launch_fwd_generic(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
-                              int64_t N, int64_t K, int q, void* y, hipStream_t st);
+                              int64_t N, int64_t K, int64_t g, int q, void* y, hipStream_t st);
 hipError_t launch_bwd_input_generic(const uint32_t* packed, const float* alpha, const void* dy, int dtype,
-                                    int64_t T, int64_t N, int64_t K, int q, void* dx, hipStream_t st);
+                                    int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, hipStream_t st);
 hipError_t launch_bwd_alpha_generic(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
-                                    int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,
-                                    hipStream_t st);
+                                    int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                    float* dalpha, hipStream_t st);
 
 // ---- matrix-core kernels (bf16 activations, need the caller's workspace) ---------------------
 size_t mfma_fwd_workspace(int64_t N, int64_t K);
 size_t mfma_bwd_input_workspace(int64_t N, int64_t K);
 hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
-                           int64_t K, int q, void* y, void* workspace, hipStream_t st);
+                           int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st);
 hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_t, const float* alpha, const void* dy,
-                                 int64_t T, int64_t N, int64_t K, int q, void* dx, void* workspace, hipStream_t st);
-size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q);
-hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
+                                 int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, void* workspace,
                                  hipStream_t st);
+size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int64_t g, int q);
+hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
+                                 int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                                 void* workspace, hipStream_t st);
 
 // ---- small-token kernels (bf16, at most 16 tokens per tile; plane-by-plane on the matrix cores) ----
 size_t small_bwd_input_workspace(int64_t T, int64_t N, int q);

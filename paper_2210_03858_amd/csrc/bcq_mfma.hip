@@ -109,7 +109,7 @@ __device__ __forceinline__ void store_word_frags(const float (&s)[32], u32x4* __
 // thread = (c = n % 32, one packed word = 32 columns k) -> four 16-byte fragment slots.
 __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ alpha, int64_t N, int64_t K,
-                                                         int q, int64_t R16 /* padded K / 16 */,
+                                                         int64_t g, int q, int64_t R16 /* padded K / 16 */,
                                                          u32x4* __restrict__ frag) {
     const int c = threadIdx.x & 31;
     const int64_t ct = blockIdx.x;
@@ -118,11 +118,12 @@ __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restr
     const int64_t w = (int64_t)blockIdx.y * 8 + (threadIdx.x >> 5);
     if (w * 2 >= R16) return;
     const bool live = (n < N) && (w < Kw);
+    const int64_t G = K / g, grp = live ? (w * 32) / g : 0;  // a packed word lies in one scale group (g % 32 == 0)
     float s[32];
 #pragma unroll
     for (int e = 0; e < 32; ++e) s[e] = 0.f;
     for (int i = 0; i < q; ++i) {
-        const float a = live ? alpha[(int64_t)i * N + n] : 0.f;
+        const float a = live ? alpha[((int64_t)i * N + n) * G + grp] : 0.f;
         const uint32_t bits = live ? packed[((int64_t)i * N + n) * Kw + w] : 0u;
 #pragma unroll
         for (int e = 0; e < 32; ++e) s[e] += ((bits >> e) & 1u) ? a : -a;
@@ -137,16 +138,17 @@ __global__ __launch_bounds__(256) void expand_fwd_kernel(const uint32_t* __restr
 template <bool TWIN>
 __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restrict__ planes,
                                                          const float* __restrict__ alpha, int64_t N, int64_t K,
-                                                         int q, int64_t R16 /* padded N / 16 */,
+                                                         int64_t g, int q, int64_t R16 /* padded N / 16 */,
                                                          u32x4* __restrict__ frag) {
     __shared__ float sa[8][256];
     const int c = threadIdx.x & 31, vl = threadIdx.x >> 5;
     const int64_t ct = blockIdx.x;  // K / 32 column tiles, exactly one packed word wide
     const int64_t Kw = K / 32, Nw = N / 32;
     const int64_t n_blk = (int64_t)blockIdx.y * 256;
+    const int64_t G = K / g, grp = (ct * 32) / g;  // the 32 columns of this block share one scale group
     for (int i = 0; i < q; ++i) {
         const int64_t n = n_blk + threadIdx.x;
-        sa[i][threadIdx.x] = (n < N) ? alpha[(int64_t)i * N + n] : 0.f;  // rows beyond N expand to zero
+        sa[i][threadIdx.x] = (n < N) ? alpha[((int64_t)i * N + n) * G + grp] : 0.f;  // rows beyond N expand to zero
     }
     __syncthreads();
     const int64_t v = (int64_t)blockIdx.y * 8 + vl;  // word index along n
@@ -435,25 +437,26 @@ static hipError_t launch_gemm(const bf16_t* A, int64_t lda, const u32x4* frag, b
 }
 
 hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
-                           int64_t K, int q, void* y, void* workspace, hipStream_t st) {
+                           int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st) {
     const int64_t R16 = round_up(K, RPAD) / 16;
     const int64_t ct = (N + 31) / 32;
     dim3 grid((unsigned)ct, (unsigned)((R16 / 2 + 7) / 8));
-    hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16, (u32x4*)workspace);
+    hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16, (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_gemm((const bf16_t*)x, K, (const u32x4*)workspace, (bf16_t*)y, N, T, N, K, R16, st);
 }
 
 hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_t, const float* alpha, const void* dy,
-                                 int64_t T, int64_t N, int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
+                                 int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, void* workspace,
+                                 hipStream_t st) {
     const int64_t R16 = round_up(N, RPAD) / 16;
     dim3 grid((unsigned)(K / 32), (unsigned)((R16 / 2 + 7) / 8));
     if (packed_t && N % 32 == 0)
-        hipLaunchKernelGGL(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, q, R16,
+        hipLaunchKernelGGL(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, g, q, R16,
                            (u32x4*)workspace);
     else
-        hipLaunchKernelGGL(expand_bwd_kernel<false>, grid, dim3(256), 0, st, packed, alpha, N, K, q, R16,
+        hipLaunchKernelGGL(expand_bwd_kernel<false>, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16,
                            (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -520,7 +523,9 @@ __global__ __launch_bounds__(256) void transpose_frag_kernel(const bf16_t* __res
 
 // XG: x comes as fragments from global memory and dy through LDS; otherwise the reverse.
 // QT: planes summed in the epilogue (q_train rounded up to 1, 2, 3, 4 or 8; extra planes are computed, not stored).
-template <bool XG, int QT>
+// FINE: partial sums are kept per 32 columns k (for scale groups that are not whole 256-column tiles) instead of
+//       per tile; they go to part[split][plane][n][8 tiles_k] and dalpha_reduce_fine_kernel adds each group's run.
+template <bool XG, int QT, bool FINE>
 __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict__ L /* activation through LDS */,
                                                         int64_t ldl, int64_t lcols,
                                                         const u32x4* __restrict__ Gfrag, int64_t T16,
@@ -679,6 +684,54 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
             for (int i = 0; i < 4; ++i) words[p][i][j] = ~(w4[i] >> (4 * (lane >> 5)));
         }
     }
+    if (FINE) {
+        // one signed sum per (plane, 32-column k tile, n): red[plane][chunk = 4 wm + i][256 n]
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float fs[QT][4];
+#pragma unroll
+            for (int p = 0; p < QT; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) fs[p][j] = 0.f;
+            if ((k0 + wm * 128 + i * 32) < K) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int bit = 8 * (v >> 2) + (v & 3);
+                        const uint32_t a = __float_as_uint(acc[i][j][v]);
+#pragma unroll
+                        for (int p = 0; p < QT; ++p)
+                            fs[p][j] += __uint_as_float(a ^ ((words[p][i][j] << (31 - bit)) & 0x80000000u));
+                    }
+            }
+#pragma unroll
+            for (int p = 0; p < QT; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float s = fs[p][j];
+                    s += __shfl_xor(s, 32);
+                    if (lane < 32) red[(p * 8 + wm * 4 + i) * 256 + wn * 128 + j * 32 + lane] = s;
+                }
+        }
+        __syncthreads();
+        const int64_t n = n0 + tid;
+        const int64_t Kc = (int64_t)tiles_k * 8;
+        if (n < N) {
+            for (int p = 0; p < q_train; ++p) {
+                float* dst = part + (((int64_t)split * q_train + p) * N + n) * Kc + (int64_t)tile_k * 8;
+                u32x4 lo, hi;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    lo[c] = __float_as_uint(red[(p * 8 + c) * 256 + tid]);
+                    hi[c] = __float_as_uint(red[(p * 8 + 4 + c) * 256 + tid]);
+                }
+                *reinterpret_cast<u32x4*>(dst) = lo;
+                *reinterpret_cast<u32x4*>(dst + 4) = hi;
+            }
+        }
+        return;
+    }
     // every accumulator is read once and added, with its sign, into the sums of all planes
     float sums[QT][4];  // [plane][n tile]
 #pragma unroll
@@ -716,31 +769,53 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
     }
 }
 
+// dalpha[pn][grp] = scale * sum over token slices and over the k tiles of group grp of part[slice][tile][pn],
+// pn = plane * N + n; `tpg` consecutive k tiles form one scale group (row-wise: all of them, G = 1).
 __global__ __launch_bounds__(256) void dalpha_reduce_kernel(const float* __restrict__ part, float* __restrict__ dalpha,
-                                                            int64_t count /* q_train * N */, int parts, float scale) {
+                                                            int64_t rows /* q_train * N */, int64_t G, int splits,
+                                                            int tiles_k, int tpg, float scale) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= count) return;
+    if (idx >= rows * G) return;
+    const int64_t pn = idx / G, grp = idx % G;
     float s = 0.f;
-    int p = 0;
-    for (; p + 8 <= parts; p += 8) {  // eight independent loads in flight, added in index order
-        float v[8];
+    for (int sp = 0; sp < splits; ++sp) {
+        const float* base = part + ((int64_t)sp * tiles_k + grp * tpg) * rows + pn;
+        int p = 0;
+        for (; p + 8 <= tpg; p += 8) {  // eight independent loads in flight, added in index order
+            float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(p + u) * count + idx];
+            for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)(p + u) * rows];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; p < tpg; ++p) s += base[(int64_t)p * rows];
     }
-    for (; p < parts; ++p) s += part[(int64_t)p * count + idx];
+    dalpha[idx] = scale * s;
+}
+
+// Fine partials part[slice][pn][Kc] (one value per 32 columns): a group is a run of cpg consecutive values.
+__global__ __launch_bounds__(256) void dalpha_reduce_fine_kernel(const float* __restrict__ part,
+                                                                 float* __restrict__ dalpha, int64_t rows, int64_t G,
+                                                                 int splits, int64_t Kc, int cpg, float scale) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * G) return;
+    const int64_t pn = idx / G, grp = idx % G;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) {
+        const float* base = part + ((int64_t)sp * rows + pn) * Kc + grp * cpg;
+        for (int c = 0; c < cpg; ++c) s += base[c];
+    }
     dalpha[idx] = scale * s;
 }
 
 struct DalphaPlan {
     int tiles_k, tiles_n, splits;
     int64_t per_split, T16;
-    bool xg;
+    bool xg, fine;
     size_t frag_bytes, part_bytes;
 };
 
-static DalphaPlan dalpha_plan(int64_t T, int64_t N, int64_t K, int q) {
+static DalphaPlan dalpha_plan(int64_t T, int64_t N, int64_t K, int64_t g, int q) {
     DalphaPlan pl;
     pl.tiles_k = (int)((K + DA_TILE - 1) / DA_TILE);
     pl.tiles_n = (int)((N + DA_TILE - 1) / DA_TILE);
@@ -755,20 +830,21 @@ static DalphaPlan dalpha_plan(int64_t T, int64_t N, int64_t K, int q) {
     pl.xg = (K <= N);
     const int64_t gcols = pl.xg ? K : N;
     pl.frag_bytes = (size_t)(((gcols + 31) / 32) * pl.T16 * 1024);
-    pl.part_bytes = (size_t)pl.splits * pl.tiles_k * q * N * sizeof(float);
+    pl.fine = (g != K) && (g % DA_TILE != 0);  // groups that are not whole k tiles need per-32-column partials
+    pl.part_bytes = (size_t)pl.splits * pl.tiles_k * q * N * sizeof(float) * (pl.fine ? 8 : 1);
     return pl;
 }
 
-size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int q) {
-    const DalphaPlan pl = dalpha_plan(T, N, K, q);
+size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int64_t g, int q) {
+    const DalphaPlan pl = dalpha_plan(T, N, K, g, q);
     return pl.frag_bytes + pl.part_bytes;
 }
 
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                 int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
-                                 hipStream_t st) {
+                                 int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                                 void* workspace, hipStream_t st) {
     const int lds = 2 * DA_STAGE;
-    const DalphaPlan pl = dalpha_plan(T, N, K, q);
+    const DalphaPlan pl = dalpha_plan(T, N, K, g, q);
     u32x4* frag = reinterpret_cast<u32x4*>(workspace);
     float* part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.frag_bytes);
     const bf16_t* gact = (const bf16_t*)(pl.xg ? x : dy);
@@ -784,38 +860,51 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     const unsigned wgs = make_tile_map(pl.tiles_k, pl.tiles_n, pl.splits, 32, 1.0, 1.0, &tmap);
     dim3 grid(wgs);
     const int qt = q_train <= 4 ? q_train : 8;
-#define BCQ_DA_LAUNCH(XGV, QTV)                                                                                       \
+#define BCQ_DA_LAUNCH(XGV, QTV, FV)                                                                                   \
     {                                                                                                                 \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
-            hipError_t ea = hipFuncSetAttribute((const void*)dalpha_kernel<XGV, QTV>,                                  \
+            hipError_t ea = hipFuncSetAttribute((const void*)dalpha_kernel<XGV, QTV, FV>,                              \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);                     \
             if (ea != hipSuccess) return ea;                                                                          \
             attr_set = true;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL((dalpha_kernel<XGV, QTV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16, packed, \
-                           part, T, N, K, q_train, tmap, pl.splits, pl.per_split);                                    \
+        hipLaunchKernelGGL((dalpha_kernel<XGV, QTV, FV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16,  \
+                           packed, part, T, N, K, q_train, tmap, pl.splits, pl.per_split);                            \
     }
-#define BCQ_DA_Q(XGV)                                  \
-    switch (qt) {                                      \
-        case 1: BCQ_DA_LAUNCH(XGV, 1) break;           \
-        case 2: BCQ_DA_LAUNCH(XGV, 2) break;           \
-        case 3: BCQ_DA_LAUNCH(XGV, 3) break;           \
-        case 4: BCQ_DA_LAUNCH(XGV, 4) break;           \
-        default: BCQ_DA_LAUNCH(XGV, 8) break;          \
+#define BCQ_DA_Q(XGV, FV)                                  \
+    switch (qt) {                                          \
+        case 1: BCQ_DA_LAUNCH(XGV, 1, FV) break;           \
+        case 2: BCQ_DA_LAUNCH(XGV, 2, FV) break;           \
+        case 3: BCQ_DA_LAUNCH(XGV, 3, FV) break;           \
+        case 4: BCQ_DA_LAUNCH(XGV, 4, FV) break;           \
+        default: BCQ_DA_LAUNCH(XGV, 8, FV) break;          \
     }
-    if (pl.xg) {
-        BCQ_DA_Q(true)
+    if (pl.fine) {
+        if (pl.xg) {
+            BCQ_DA_Q(true, true)
+        } else {
+            BCQ_DA_Q(false, true)
+        }
     } else {
-        BCQ_DA_Q(false)
+        if (pl.xg) {
+            BCQ_DA_Q(true, false)
+        } else {
+            BCQ_DA_Q(false, false)
+        }
     }
 #undef BCQ_DA_Q
 #undef BCQ_DA_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int64_t count = (int64_t)q_train * N;
-    hipLaunchKernelGGL(dalpha_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
-                       (const float*)part, dalpha, count, pl.splits * pl.tiles_k, grad_scale);
+    const int64_t rows = (int64_t)q_train * N, G = K / g;
+    const dim3 rgrid((unsigned)((rows * G + 255) / 256));
+    if (pl.fine)
+        hipLaunchKernelGGL(dalpha_reduce_fine_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
+                           pl.splits, (int64_t)pl.tiles_k * 8, (int)(g / 32), grad_scale);
+    else
+        hipLaunchKernelGGL(dalpha_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
+                           pl.splits, pl.tiles_k, (int)(g == K ? pl.tiles_k : g / DA_TILE), grad_scale);
     return hipGetLastError();
 }
 

@@ -46,10 +46,10 @@ def tol_for(dtype):
     return TOL_F32 if dtype == "f32" else TOL_BF16
 
 
-def make_case(config, kind, T, N, K, q, dtype, oracle, outliers=False, extra=0):
-    """Seeded layer + activations, quantized by the oracle."""
+def make_case(config, kind, T, N, K, q, dtype, oracle, outliers=False, extra=0, g=None):
+    """Seeded layer + activations, quantized by the oracle (g: group size along K, None = row-wise)."""
     W = synth.weights(config, kind, N, K, outliers=outliers, extra=extra)
-    alpha, planes = oracle.quantize(W, q)
+    alpha, planes = oracle.quantize(W, q, g=g)
     x = synth.activations(config, kind, T, K, 1, dtype, extra)
     dy = synth.activations(config, kind, T, N, 2, dtype, extra)
     return W, alpha, planes, oracle.pack(planes), x, dy

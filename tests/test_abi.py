@@ -39,7 +39,7 @@ def test_status_strings(lib):
         s = lib.bcq_status_string(code)
         assert s and s not in seen
         seen.add(s)
-    assert lib.bcq_abi_version() >= 1
+    assert lib.bcq_abi_version() >= 2
 
 
 A = 0x1000  # a fake, aligned, never dereferenced pointer
@@ -85,6 +85,29 @@ def test_argument_errors_before_device(lib):
     assert lib.bcq_quantize(A, N, K, q, A, A, A + 1, None, 0, None) == 4
     # workspace too small
     assert lib.bcq_quantize(A, N, K, q, A, A, None, A, 4, None) == 5
+
+
+def test_group_size_errors_before_device(lib):
+    """g must be a multiple of 32 in [32, K] that divides K; everything else is as for the row-wise calls."""
+    q, N, K, T = 3, 64, 192, 8
+    out = ctypes.c_size_t(0)
+    i64 = ctypes.c_int64
+    for g in (0, 16, 48, 128, 384, -64):
+        assert lib.bcq_workspace_bytes_grouped(1, T, N, K, i64(g), q, 1, ctypes.byref(out)) == 2, g
+        assert lib.bcq_quantize_grouped(A, N, K, i64(g), q, A, A, None, None, 0, None) == 2, g
+        assert lib.bcq_linear_fwd_grouped(A, A, A, 1, T, N, K, i64(g), q, A, None, 0, None) == 2, g
+        assert lib.bcq_linear_bwd_input_grouped(A, None, A, A, 1, T, N, K, i64(g), q, A, None, 0, None) == 2, g
+        assert lib.bcq_linear_bwd_alpha_grouped(A, A, A, 1, T, N, K, i64(g), q, q, 1.0, A, None, 0, None) == 2, g
+    for g in (32, 64, 96, 192):
+        assert lib.bcq_workspace_bytes_grouped(3, 64, N, K, i64(g), q, 1, ctypes.byref(out)) == 0, g
+    assert lib.bcq_linear_fwd_grouped(None, A, A, 1, T, N, K, i64(64), q, A, None, 0, None) == 1
+    assert lib.bcq_linear_bwd_alpha_grouped(A, A, A, 1, T, N, K, i64(64), q, q + 1, 1.0, A, None, 0, None) == 2
+    assert lib.bcq_linear_fwd_grouped(A, A + 4, A, 1, T, N, K, i64(64), q, A, None, 0, None) == 4
+    # a group-wise dalpha workspace with per-32-column partials is larger than the row-wise one
+    rw, gw = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert lib.bcq_workspace_bytes(3, 512, 256, 512, q, 1, ctypes.byref(rw)) == 0
+    assert lib.bcq_workspace_bytes_grouped(3, 512, 256, 512, i64(64), q, 1, ctypes.byref(gw)) == 0
+    assert gw.value > rw.value
 
 
 def test_no_device_is_reported(lib):
