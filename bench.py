@@ -38,6 +38,12 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload number (2 = GPT-2-medium block, the headline)")
     ap.add_argument("--tokens", type=int, default=0, help="override the token count of the workload")
     ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
+    ap.add_argument("--g", type=int, default=0,
+                    help="group size of the scales along K (Table 4); 0 = row-wise (g = h_in), the headline workload; "
+                         "a layer with K < g uses g = K")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the two context measurements (device-to-device copy, plain bf16 GEMMs of the same "
+                         "shapes through the vendor BLAS that PyTorch links)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
     ap.add_argument("--graph", action="store_true",
@@ -89,10 +95,11 @@ def main():
     for rep, kind in [(r, k) for r in range(replicas) for k in kinds]:
         N, K = synth.layer_shape(h, kind)
         W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"], extra=rep)).cuda()
+        g = min(args.g, K) if args.g else K
         e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        bcq.bcq_quantize(W, q)  # warm
+        bcq.bcq_quantize_grouped(W, q, g)  # warm
         e0.record()
-        alpha, packed, _ = bcq.bcq_quantize(W, q)
+        alpha, packed, _ = bcq.bcq_quantize_grouped(W, q, g)
         e1.record()
         twin = bcq.bcq_pack_transposed(packed) if N % 32 == 0 else None
         e2.record()
@@ -104,24 +111,26 @@ def main():
         dy = torch.from_numpy(synth.activations(args.config, kind, T, N, 2, dtype)).cuda().to(tdtype)
         ws = {}
         for op in (1, 2, 3):
-            nbytes = bcq.workspace_bytes(op, T, N, K, q, code)
+            nbytes = bcq.workspace_bytes_grouped(op, T, N, K, g, q, code)
             ws[op] = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device="cuda")
-        layers.append(dict(kind=kind, N=N, K=K, alpha=alpha, packed=packed, twin=twin, x=x, dy=dy, ws=ws,
+        layers.append(dict(kind=kind, N=N, K=K, g=g, alpha=alpha, packed=packed, twin=twin, x=x, dy=dy, ws=ws,
                            y=torch.empty((T, N), dtype=tdtype, device="cuda"),
                            dx=torch.empty((T, K), dtype=tdtype, device="cuda"),
-                           da=torch.empty((q, N), dtype=torch.float32, device="cuda")))
+                           da=torch.empty((q, N, K // g), dtype=torch.float32, device="cuda")))
         del W
 
     ops = ("fwd", "bwd_input", "bwd_alpha")
 
     def run_op(L, op):
+        # the row-wise C entry points forward to the grouped ones with g = K, so one call form serves both
         if op == "fwd":
-            bcq.bcq_linear_fwd(L["packed"], L["alpha"], L["x"], y=L["y"], workspace=L["ws"][1])
+            bcq.bcq_linear_fwd_grouped(L["packed"], L["alpha"], L["x"], L["g"], y=L["y"], workspace=L["ws"][1])
         elif op == "bwd_input":
-            bcq.bcq_linear_bwd_input(L["packed"], L["alpha"], L["dy"], packed_t=L["twin"], dx=L["dx"],
-                                     workspace=L["ws"][2])
+            bcq.bcq_linear_bwd_input_grouped(L["packed"], L["alpha"], L["dy"], L["g"], packed_t=L["twin"], dx=L["dx"],
+                                             workspace=L["ws"][2])
         else:
-            bcq.bcq_linear_bwd_alpha(L["packed"], L["x"], L["dy"], dalpha=L["da"], workspace=L["ws"][3])
+            bcq.bcq_linear_bwd_alpha_grouped(L["packed"], L["x"], L["dy"], L["g"], dalpha=L["da"],
+                                             workspace=L["ws"][3])
 
     def step(events=None, only=None):
         """One pass of the hot path.  With `events`, HIP events bracket every op (or only the ops of family `only`)."""
@@ -195,7 +204,7 @@ def main():
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
         roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
-                    "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)),
+                    "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)) if not args.g else None,
                     "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
                     "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
 
@@ -214,6 +223,36 @@ def main():
                     "algorithmic": "per op and layer: q*N*K/8 plane bytes + 4*q*N + activations; planes are read once "
                                    "by each of fwd, dx, dalpha"}
 
+    # ---------------- context (not a target, not part of the library): what a plain copy and plain bf16 GEMMs of
+    # the same shapes reach on this GPU in this run
+    context = None
+    if not args.no_context and not small and dtype == "bf16":
+        def timed(fn, n=10):
+            fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        copy_ms = timed(lambda: dst.copy_(src))
+        del src, dst
+        gemm_ms = 0.0
+        for L in layers[:len(kinds)]:
+            Wd = torch.randn((L["N"], L["K"]), dtype=tdtype, device="cuda")
+            gemm_ms += timed(lambda: torch.matmul(L["x"], Wd.t()))          # y  = x  W^T
+            gemm_ms += timed(lambda: torch.matmul(L["dy"], Wd))             # dx = dy W
+            gemm_ms += timed(lambda: torch.matmul(L["dy"].t(), L["x"]))     # dW-shaped product behind dalpha
+            del Wd
+        context = {"d2d_copy_GBps": round(2 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1),
+                   "vendor_bf16_gemm_tflops": round(flops_step / replicas / (gemm_ms * 1e-3) / 1e12, 1),
+                   "vendor_bf16_gemm_ms_per_step": round(gemm_ms, 4),
+                   "note": "torch.matmul on dense bf16 weights of the same shapes (3 GEMMs per layer), events around "
+                           "10 back-to-back calls each; read+write bytes for the 1 GiB copy"}
+
     # ---------------- CPU oracle on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -224,14 +263,15 @@ def main():
                 break
             N, K = synth.layer_shape(h, kind)
             W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
-            a_ref, planes_ref = oracle.quantize(W, q)
+            gl = min(args.g, K) if args.g else K
+            a_ref, planes_ref = oracle.quantize(W, q, g=gl)
             Ts = min(T, 4096)
             xs = synth.activations(args.config, kind, T, K, 1, dtype)[:Ts]
             dys = synth.activations(args.config, kind, T, N, 2, dtype)[:Ts]
             c0 = time.perf_counter()
             oracle.fwd(a_ref, planes_ref, xs)
             oracle.bwd_input(a_ref, planes_ref, dys)
-            oracle.bwd_alpha(planes_ref, xs, dys)
+            oracle.bwd_alpha(planes_ref, xs, dys, g=gl)
             spent += time.perf_counter() - c0
             flops_done += 6.0 * Ts * N * K
             done.append("%s %dx%d x %d tokens" % (kind, N, K, Ts))
@@ -252,12 +292,14 @@ def main():
         "vs_baseline": None,
         "dtype": dtype,
         "data": "synthetic",
-        "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s activations, T=%d tokens; fwd+dx+dalpha"
-                               % (args.config, h, "/".join(kinds), q, dtype, T),
-                   "h": h, "q": q, "tokens": T, "weights_per_block": weights_total // replicas,
+        "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s scales, %s activations, T=%d tokens; "
+                               "fwd+dx+dalpha" % (args.config, h, "/".join(kinds), q,
+                                                  ("g=%d group-wise" % args.g) if args.g else "row-wise", dtype, T),
+                   "h": h, "q": q, "tokens": T, "g": args.g or "h_in", "weights_per_block": weights_total // replicas,
                    "layer_stack_replicas": replicas, "hip_graph": graph is not None},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "context": context,
         "per_op": per_op,
         "setup": {k: round(v, 4) for k, v in setup_ms.items()},
         "packed_weight_bytes": q * weights_total // 8,
