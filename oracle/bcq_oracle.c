@@ -352,3 +352,166 @@ void orc_bwd_alpha_g_rows(const int8_t* planes, const float* x, const float* dy,
             }
         }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Alternating quantizer (Appendix C, "Alternating Method", Eq. ap4).  Per vector w of length n:
+ *   start from the greedy (alpha, B);
+ *   repeat `iters` times (the paper uses 15):
+ *     (1) alpha <- (B^T B)^{-1} B^T w                      least-squares refit, Eq. ap4
+ *     (2) every element takes the sign pattern whose level sum_i +-alpha_i is nearest to w_k
+ *         (the paper finds it by binary search over the sorted 2^q levels; here all 2^q levels
+ *         are compared, which gives the same pattern)
+ * Readings of silent points:
+ *   - the iteration arithmetic is fp64; alpha is rounded to fp32 once, at the end;
+ *   - the returned alpha is the one of the last refit (1) and the returned B the one of the last
+ *     re-assignment (2); no extra refit follows;
+ *   - if step (2) changes nothing the pair is a fixed point and the loop stops (more iterations
+ *     would repeat it exactly);
+ *   - if B^T B is singular (two planes equal or opposite, e.g. an all-zero vector) the loop stops
+ *     before that refit and the current (alpha, B) stay; singular = a Cholesky pivot <= 1e-9 n;
+ *   - ties between two levels go to the larger level, ties between equal levels to the larger
+ *     pattern index c = sum_i [b_i = +1] 2^i (consistent with sign(0) = +1).
+ * margin[0]: smallest relative gap between the best and the second-best level over all elements
+ *            and iterations (exact ties at w_k = 0 between the mirror levels +-v are not counted:
+ *            they are resolved by the rule above, whatever the rounding of alpha);
+ * margin[1]: smallest round_margin() of the returned alpha_i.
+ * ------------------------------------------------------------------------------------------ */
+static void alternating_row(const float* w, int64_t n, int q, int iters, float* alpha_out,
+                            int8_t* b_out, int64_t plane_stride, double* margin, double* err_trace,
+                            int* iters_done, double* r, uint8_t* code) {
+    double a[8], m_dec = 1.0;
+    greedy_row(w, n, q, NULL, NULL, alpha_out, b_out, plane_stride, NULL, r);
+    for (int i = 0; i < q; ++i) a[i] = (double)alpha_out[i];
+    for (int64_t k = 0; k < n; ++k) {
+        uint8_t c = 0;
+        for (int i = 0; i < q; ++i)
+            if (b_out[(int64_t)i * plane_stride + k] > 0) c |= (uint8_t)(1u << i);
+        code[k] = c;
+    }
+    const int levels = 1 << q;
+    int done = 0;
+    for (int it = 0; it < iters; ++it) {
+        if (err_trace) { /* squared error before this iteration */
+            double e = 0.0;
+            for (int64_t k = 0; k < n; ++k) {
+                double v = 0.0;
+                for (int i = 0; i < q; ++i) v += ((code[k] >> i) & 1) ? a[i] : -a[i];
+                e += ((double)w[k] - v) * ((double)w[k] - v);
+            }
+            err_trace[2 * it] = e;
+        }
+        /* (1) Eq. ap4: Gram matrix and right-hand side, then Cholesky solve */
+        double G[8][8], rhs[8], L[8][8], y[8];
+        for (int i = 0; i < q; ++i) {
+            for (int j = 0; j <= i; ++j) {
+                double s = 0.0;
+                for (int64_t k = 0; k < n; ++k)
+                    s += (((code[k] >> i) & 1) == ((code[k] >> j) & 1)) ? 1.0 : -1.0;
+                G[i][j] = s;
+            }
+            double s = 0.0;
+            for (int64_t k = 0; k < n; ++k) s += ((code[k] >> i) & 1) ? (double)w[k] : -(double)w[k];
+            rhs[i] = s;
+        }
+        int singular = 0;
+        for (int j = 0; j < q && !singular; ++j) {
+            double d = G[j][j];
+            for (int p = 0; p < j; ++p) d -= L[j][p] * L[j][p];
+            if (!(d > 1e-9 * (double)n)) { singular = 1; break; }
+            L[j][j] = sqrt(d);
+            for (int i = j + 1; i < q; ++i) {
+                double s = G[i][j];
+                for (int p = 0; p < j; ++p) s -= L[i][p] * L[j][p];
+                L[i][j] = s / L[j][j];
+            }
+        }
+        if (singular) break;
+        for (int i = 0; i < q; ++i) {
+            double s = rhs[i];
+            for (int p = 0; p < i; ++p) s -= L[i][p] * y[p];
+            y[i] = s / L[i][i];
+        }
+        for (int i = q - 1; i >= 0; --i) {
+            double s = y[i];
+            for (int p = i + 1; p < q; ++p) s -= L[p][i] * a[p];
+            a[i] = s / L[i][i];
+        }
+        if (err_trace) { /* squared error after the refit */
+            double e = 0.0;
+            for (int64_t k = 0; k < n; ++k) {
+                double v = 0.0;
+                for (int i = 0; i < q; ++i) v += ((code[k] >> i) & 1) ? a[i] : -a[i];
+                e += ((double)w[k] - v) * ((double)w[k] - v);
+            }
+            err_trace[2 * it + 1] = e;
+        }
+        /* (2) nearest level for every element */
+        double lv[256], scale = 0.0;
+        for (int c = 0; c < levels; ++c) {
+            double v = 0.0;
+            for (int i = 0; i < q; ++i) v += ((c >> i) & 1) ? a[i] : -a[i];
+            lv[c] = v;
+        }
+        for (int i = 0; i < q; ++i) scale += fabs(a[i]);
+        int changed = 0;
+        for (int64_t k = 0; k < n; ++k) {
+            double x = (double)w[k];
+            int best = levels - 1;
+            double bd = fabs(x - lv[best]);
+            for (int c = levels - 2; c >= 0; --c) {
+                double d = fabs(x - lv[c]);
+                if (d < bd || (d == bd && lv[c] > lv[best])) { best = c; bd = d; }
+            }
+            double second = INFINITY;
+            for (int c = 0; c < levels; ++c)
+                if (c != best) { double d = fabs(x - lv[c]); if (d < second) second = d; }
+            double gap = second - bd;
+            int mirror_tie = (gap == 0.0 && x == 0.0);
+            if (!mirror_tie && scale > 0.0 && gap / scale < m_dec) m_dec = gap / scale;
+            if ((uint8_t)best != code[k]) { code[k] = (uint8_t)best; changed = 1; }
+        }
+        done = it + 1;
+        if (!changed) break;
+    }
+    double m_round = 1.0;
+    for (int i = 0; i < q; ++i) {
+        alpha_out[i] = (float)a[i];
+        double rm = round_margin(fabs(a[i]));
+        if (rm < m_round) m_round = rm;
+        for (int64_t k = 0; k < n; ++k)
+            b_out[(int64_t)i * plane_stride + k] = ((code[k] >> i) & 1) ? (int8_t)1 : (int8_t)-1;
+    }
+    if (margin) { margin[0] = m_dec; margin[1] = m_round; }
+    if (iters_done) *iters_done = done;
+}
+
+/* W[N][K] -> alpha[q][N][K/g], planes[q][N][K]; margin[N*K/g][2], iters_done[N*K/g] optional. */
+void orc_quantize_alternating(const float* W, int64_t N, int64_t K, int64_t g, int q, int iters,
+                              float* alpha, int8_t* planes, double* margin, int* iters_done) {
+    int64_t V = N * (K / g);
+#pragma omp parallel
+    {
+        double* r = (double*)malloc(sizeof(double) * (size_t)g);
+        uint8_t* code = (uint8_t*)malloc((size_t)g);
+        float a[8];
+#pragma omp for schedule(static)
+        for (int64_t v = 0; v < V; ++v) {
+            alternating_row(W + v * g, g, q, iters, a, planes + v * g, N * K, margin ? margin + 2 * v : NULL,
+                            NULL, iters_done ? iters_done + v : NULL, r, code);
+            for (int i = 0; i < q; ++i) alpha[(int64_t)i * V + v] = a[i];
+        }
+        free(r);
+        free(code);
+    }
+}
+
+/* One vector with the squared error before every iteration and after every refit:
+ * err_trace[2 it], err_trace[2 it + 1], it < iters (unused entries stay as passed in). */
+void orc_alternating_row_trace(const float* w, int64_t n, int q, int iters, float* alpha_out,
+                               int8_t* planes_row, double* err_trace, int* iters_done) {
+    double* r = (double*)malloc(sizeof(double) * (size_t)n);
+    uint8_t* code = (uint8_t*)malloc((size_t)n);
+    alternating_row(w, n, q, iters, alpha_out, planes_row, n, NULL, err_trace, iters_done, r, code);
+    free(r);
+    free(code);
+}

@@ -246,3 +246,37 @@ def storage_bytes(N, K, q, g=None):
     """Bytes of a BCQ matrix with 1-bit signs and fp32 scales: q*(N*K/8 + 4*N*K/g) (Table 1)."""
     g = K if g is None else g
     return q * (N * K // 8 + 4 * N * K // g)
+
+
+def quantize_alternating(W, q, iters=15, g=None, with_margin=False):
+    """Alternating quantizer (Appendix C, Eq. ap4): greedy start, then `iters` rounds of least-squares refit of
+    alpha and nearest-level re-assignment of the signs.  Returns alpha[q,N] (or [q,N,K/g]) fp32, planes[q,N,K];
+    with_margin also margin[N*K/g, 2] (decision gap, fp32 rounding margin) and the iterations done per vector."""
+    W = _f32(W)
+    N, K = W.shape
+    g = _group(K, g)
+    assert 1 <= q <= 8
+    V = N * (K // g)
+    alpha = np.empty((q, N, K // g), np.float32)
+    planes = np.empty((q, N, K), np.int8)
+    margin = np.empty((V, 2), np.float64) if with_margin else None
+    done = np.empty((V,), np.int32) if with_margin else None
+    _load().orc_quantize_alternating(_p(W), _I64(N), _I64(K), _I64(g), _INT(q), _INT(iters), _p(alpha), _p(planes),
+                                     _p(margin) if with_margin else None, _p(done) if with_margin else None)
+    if g == K:
+        alpha = alpha[:, :, 0].copy()
+    return (alpha, planes, margin, done) if with_margin else (alpha, planes)
+
+
+def alternating_row_trace(w, q, iters=15):
+    """One vector: (alpha[q], planes[q,n], err[iters,2], iterations done); err[it] = squared error before
+    iteration it and after its refit (NaN where the loop had already stopped)."""
+    w = _f32(w)
+    n = w.shape[0]
+    alpha = np.empty((q,), np.float32)
+    planes = np.empty((q, n), np.int8)
+    err = np.full((iters, 2), np.nan, np.float64)
+    done = ctypes.c_int(0)
+    _load().orc_alternating_row_trace(_p(w), _I64(n), _INT(q), _INT(iters), _p(alpha), _p(planes), _p(err),
+                                      ctypes.byref(done))
+    return alpha, planes, err, int(done.value)

@@ -446,3 +446,100 @@ def test_groupwise_bwd_alpha_crossform_fd_additivity(oracle):
     assert first.shape == (1, N, K // g) and np.array_equal(first[0], da[0])
     rows = np.array([10, 0, 4])
     assert np.array_equal(oracle.bwd_alpha_rows(planes, x, dy, rows, g=g), da[:, rows])
+
+
+# ---------------------------------------------------------------- alternating quantizer (Appendix C, Eq. ap4)
+
+def _levels(alpha64):
+    q = alpha64.shape[0]
+    codes = np.arange(1 << q)
+    signs = np.where((codes[:, None] >> np.arange(q)[None, :]) & 1, 1.0, -1.0)  # [2^q, q]
+    return signs @ alpha64, signs
+
+
+def test_alternating_q1_and_zero_iterations_are_greedy(oracle):
+    """q = 1 has the analytic optimum of Eq. ap1, which is the greedy result; zero iterations return the
+    greedy start unchanged for any q."""
+    W = (_rng(70).standard_normal((12, 160)) * 0.02).astype(np.float32)
+    a1, b1 = oracle.quantize_alternating(W, 1)
+    ag, bg = oracle.quantize(W, 1)
+    assert np.array_equal(b1, bg)
+    assert np.all(np.abs(a1.astype(np.float64) - ag) <= np.spacing(ag))
+    for q in (2, 4):
+        a0, b0 = oracle.quantize_alternating(W, q, iters=0)
+        ag, bg = oracle.quantize(W, q)
+        assert np.array_equal(a0, ag) and np.array_equal(b0, bg)
+
+
+@pytest.mark.parametrize("q", [2, 3, 4])
+def test_alternating_error_never_increases(oracle, q):
+    """Both half steps are exact minimisations (Eq. ap4 over alpha, nearest level over the signs), so the squared
+    error is non-increasing along the whole trace and ends at or below the greedy error."""
+    W = (_rng(71 + q).standard_normal((6, 192)) * 0.02).astype(np.float32)
+    for n in range(W.shape[0]):
+        alpha, planes, err, done = oracle.alternating_row_trace(W[n], q)
+        assert 1 <= done <= 15
+        seq = err[:done].reshape(-1)
+        assert np.all(np.diff(seq) <= 1e-15 * seq[0])
+        ag, bg = oracle.quantize(W[n:n + 1], q)
+        e_greedy = float(((W[n].astype(np.float64) - oracle.dequant(ag, bg)[0]) ** 2).sum())
+        assert seq[0] == pytest.approx(e_greedy, rel=1e-12)       # the trace starts from the greedy pair
+        e_final = float(((W[n].astype(np.float64) - oracle.dequant(alpha[:, None], planes[:, None, :])[0]) ** 2).sum())
+        assert e_final <= e_greedy * (1 + 1e-6)
+        assert e_final < 0.97 * e_greedy                           # and really improves Gaussian rows
+
+
+def test_alternating_fixed_point_is_least_squares_and_nearest_level(oracle):
+    """When the loop stops at a fixed point, alpha is the least-squares solution of Eq. ap4 for the returned B
+    (numpy lstsq) and every element carries the nearest of the 2^q levels (brute force)."""
+    W = (_rng(75).standard_normal((40, 96)) * 0.02).astype(np.float32)
+    q = 3
+    alpha, planes, margin, done = oracle.quantize_alternating(W, q, iters=60, with_margin=True)
+    checked = 0
+    for n in range(W.shape[0]):
+        if done[n] >= 60:
+            continue
+        B = planes[:, n, :].astype(np.float64).T            # [n, q]
+        ls = np.linalg.lstsq(B, W[n].astype(np.float64), rcond=None)[0]
+        assert np.allclose(alpha[:, n], ls, rtol=1e-6, atol=1e-12)
+        lv, signs = _levels(ls)
+        nearest = np.abs(W[n].astype(np.float64)[:, None] - lv[None, :]).argmin(axis=1)
+        assert np.array_equal(signs[nearest].T, planes[:, n, :].astype(np.float64))
+        checked += 1
+    assert checked >= 30
+
+
+def test_alternating_recovers_an_exactly_representable_vector(oracle):
+    """w = sum_i a_i b_i with well separated scales: the greedy planes are the true ones but its scales are
+    means of |residual| and miss; one least-squares refit (Eq. ap4) recovers the scales exactly."""
+    rng = _rng(76)
+    a_true = np.array([1.0, 0.375, 0.125])
+    B = rng.choice([-1.0, 1.0], size=(3, 257 * 0 + 224))
+    w = (a_true[:, None] * B).sum(axis=0).astype(np.float32)
+    alpha, planes = oracle.quantize_alternating(w[None, :], 3)
+    assert np.array_equal(planes[:, 0, :], B.astype(np.int8))
+    assert np.array_equal(alpha[:, 0], a_true.astype(np.float32))
+    ag, _ = oracle.quantize(w[None, :], 3)
+    assert not np.array_equal(ag[:, 0], a_true.astype(np.float32))
+
+
+def test_alternating_degenerate_vectors(oracle):
+    """All-zero vector: all planes are equal, B^T B is singular, the greedy pair stays.  Zero elements sit midway
+    between the mirror levels +-v and take the larger one."""
+    W = (_rng(77).standard_normal((3, 64)) * 0.02).astype(np.float32)
+    W[0] = 0.0
+    W[1, ::4] = 0.0
+    alpha, planes, margin, done = oracle.quantize_alternating(W, 2, with_margin=True)
+    assert done[0] == 0 and np.all(alpha[:, 0] == 0) and np.all(planes[:, 0] == 1)
+    lv, signs = _levels(alpha[:, 1].astype(np.float64))
+    zero_codes = planes[:, 1, ::4].astype(np.float64).T @ alpha[:, 1].astype(np.float64)
+    assert np.all(zero_codes > 0) and np.allclose(zero_codes, np.min(lv[lv > 0]))
+    assert np.all(margin[:, 0] > 0)   # mirror ties are resolved by rule and are not counted as fragile
+
+
+def test_alternating_groupwise_is_vectorwise(oracle):
+    W = (_rng(78).standard_normal((5, 256)) * 0.02).astype(np.float32)
+    a, b = oracle.quantize_alternating(W, 3, g=64)
+    a2, b2 = oracle.quantize_alternating(W.reshape(20, 64), 3)
+    assert a.shape == (3, 5, 4)
+    assert np.array_equal(a.reshape(3, 20), a2) and np.array_equal(b.reshape(3, 20, 64), b2)
