@@ -75,7 +75,7 @@ typedef enum {
 /* Static, NUL-terminated description of a status code. */
 const char* bcq_status_string(bcq_status s);
 
-/* ABI version, bumped on any signature change or addition (2: *_grouped entry points). */
+/* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -105,6 +105,18 @@ bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alph
 bcq_status bcq_quantize_grouped(const float* W, int64_t N, int64_t K, int64_t g, int q, float* alpha,
                                 uint32_t* packed, int8_t* planes_i8, void* workspace, size_t workspace_bytes,
                                 void* stream);
+
+/* Alternating quantizer (Appendix C, "Alternating Method", Eq. ap4): the greedy result of every length-g vector
+ * is refined by `iters` rounds (the paper uses 15) of (1) least-squares refit alpha = (B^T B)^{-1} B^T w and
+ * (2) re-assignment of every element to the nearest of the 2^q levels sum_i +-alpha_i.  fp64 throughout, alpha
+ * rounded to fp32 once at the end (it may come out negative or zero).  The loop stops at a fixed point, and before
+ * a refit whose B^T B is singular (then the current pair stays, e.g. the greedy pair of an all-zero vector).
+ * Ties between two levels go to the larger level.  iters = 0 returns the greedy result.  Arguments, layouts,
+ * limits and the status word as bcq_quantize_grouped (g = K: row-wise); 0 <= iters <= BCQ_ALTERNATING_MAX_ITERS. */
+#define BCQ_ALTERNATING_MAX_ITERS 1000
+bcq_status bcq_quantize_alternating(const float* W, int64_t N, int64_t K, int64_t g, int q, int iters, float* alpha,
+                                    uint32_t* packed, int8_t* planes_i8, void* workspace, size_t workspace_bytes,
+                                    void* stream);
 
 /* Bit-plane pack (Table 1 gives the index order B:(q, h_out, h_in); footnote of Section 3: contiguous rows).
  *   planes_i8 [q][N][K] int8, in.  Only the sign of each byte is read: v >= 0 -> bit 1 (+1), v < 0 -> bit 0.

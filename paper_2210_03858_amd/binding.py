@@ -20,7 +20,7 @@ QUANTIZE_MAX_K = 16384
 EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_quantize", "bcq_pack",
            "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha",
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
-           "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped")
+           "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating")
 
 _lib = None
 
@@ -57,6 +57,7 @@ def load():
     lib.bcq_linear_fwd_grouped.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_bwd_input_grouped.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_bwd_alpha_grouped.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, i32, f32, vp, vp, sz, vp]
+    lib.bcq_quantize_alternating.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -298,3 +299,26 @@ def bcq_linear_bwd_alpha_grouped(packed, x, dy, g, q_train=None, grad_scale=1.0,
                                                float(grad_scale), _ptr(dalpha), wp, wb, _stream()),
            "bcq_linear_bwd_alpha_grouped")
     return dalpha
+
+
+def bcq_quantize_alternating(W, q, iters=15, g=None, alpha=None, packed=None, planes_i8=None, want_planes=False,
+                             workspace=None):
+    """Alternating quantizer (greedy start + `iters` rounds of least-squares refit and nearest-level re-assignment)
+    -> (alpha[q,N,K/g] f32, packed[q,N,K/32], planes_i8 or None); g=None is row-wise (alpha[q,N,1])."""
+    N, K = W.shape
+    g = K if g is None else int(g)
+    G = K // max(g, 1)
+    _need(W, torch.float32, (N, K), "W")
+    dev = W.device
+    alpha = torch.empty((q, N, G), dtype=torch.float32, device=dev) if alpha is None else alpha
+    packed = torch.empty((q, N, K // 32), dtype=torch.int32, device=dev) if packed is None else packed
+    if planes_i8 is None and want_planes:
+        planes_i8 = torch.empty((q, N, K), dtype=torch.int8, device=dev)
+    _need(alpha, torch.float32, (q, N, G), "alpha")
+    _need(packed, torch.int32, (q, N, K // 32), "packed")
+    if planes_i8 is not None:
+        _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_quantize_alternating(_ptr(W), N, K, g, q, int(iters), _ptr(alpha), _ptr(packed),
+                                           _ptr(planes_i8), wp, wb, _stream()), "bcq_quantize_alternating")
+    return alpha, packed, planes_i8

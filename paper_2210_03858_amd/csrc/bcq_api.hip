@@ -108,7 +108,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 2; }
+int bcq_abi_version(void) { return 3; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {
@@ -152,6 +152,26 @@ bcq_status bcq_quantize_grouped(const float* W, int64_t N, int64_t K, int64_t g,
 bcq_status bcq_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                         int8_t* planes_i8, void* workspace, size_t workspace_bytes, void* stream) {
     return bcq_quantize_grouped(W, N, K, K, q, alpha, packed, planes_i8, workspace, workspace_bytes, stream);
+}
+
+bcq_status bcq_quantize_alternating(const float* W, int64_t N, int64_t K, int64_t g, int q, int iters, float* alpha,
+                                    uint32_t* packed, int8_t* planes_i8, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+    if (!W || !alpha || !packed) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
+    if (g > BCQ_QUANTIZE_MAX_K || iters < 0 || iters > BCQ_ALTERNATING_MAX_ITERS) return BCQ_ERR_SHAPE;
+    const int64_t vectors = N * (K / g);
+    if (vectors > 0x7FFFFFFF) return BCQ_ERR_SHAPE;
+    if (misaligned(W) || misaligned(alpha) || misaligned(packed) || misaligned(planes_i8)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_QUANTIZE, 1, N, K, g, q, BCQ_F32));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_quantize_alternating(W, vectors, g, q, iters, alpha, packed, planes_i8, (int*)workspace,
+                                                 (hipStream_t)stream));
 }
 
 bcq_status bcq_pack(const int8_t* planes_i8, int64_t N, int64_t K, int q, uint32_t* packed, void* stream) {

@@ -37,6 +37,10 @@ hipError_t launch_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, 
 hipError_t launch_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                            int8_t* planes, int* status_word, hipStream_t st);
 
+// Alternating quantizer over V vectors of length n (W viewed as [V][n]); alpha[q][V], packed[q][V][n/32].
+hipError_t launch_quantize_alternating(const float* W, int64_t V, int64_t n, int q, int iters, float* alpha,
+                                       uint32_t* packed, int8_t* planes, int* status_word, hipStream_t st);
+
 // Scales are alpha[q][N][K / g] (g = group size along K, a multiple of 32 that divides K; g = K is the row-wise
 // case alpha[q][N]); the scale gradient has the same shape.
 
