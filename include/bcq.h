@@ -75,7 +75,7 @@ typedef enum {
 /* Static, NUL-terminated description of a status code. */
 const char* bcq_status_string(bcq_status s);
 
-/* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating). */
+/* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -173,6 +173,30 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
 bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                         int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
                                         float* dalpha, void* workspace, size_t workspace_bytes, void* stream);
+
+/* One AdamW step (Appendix A: AdamW with a linear-decay learning rate, the schedule being the caller's: pass the
+ * step's lr).  Decoupled weight decay, bias-corrected moments, t = step >= 1:
+ *     m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2;
+ *     alpha <- alpha - lr * ( (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps) + weight_decay * alpha ).
+ * BCQ_ERR_SHAPE: beta outside [0,1), step < 1, eps < 0, NaN lr or weight_decay. */
+typedef struct bcq_adamw {
+    float lr, beta1, beta2, eps, weight_decay;
+    int64_t step;
+} bcq_adamw;
+
+/* alpha, m, v [count] fp32 in/out (device), dalpha [count] fp32 in: the update above, element-wise.  Only the
+ * trained scales take part: with q_train < q pass the first q_train planes (they are contiguous). */
+bcq_status bcq_alpha_adamw_step(float* alpha, const float* dalpha, float* m, float* v, int64_t count,
+                                const bcq_adamw* opt, void* stream);
+
+/* bcq_linear_bwd_alpha_grouped followed by the AdamW step on alpha[0 .. q_train) in the same call (Section 4.1:
+ * only the scales are trained; Section 4.2: alpha_1 only = q_train 1).  dalpha [q_train][N][K/g] is still written;
+ * alpha, m, v [q_train][N][K/g] fp32 are updated in place.  On the matrix-core path the update happens inside the
+ * final reduction of the gradient (no extra kernel, no re-read of dalpha). */
+bcq_status bcq_linear_bwd_alpha_adamw(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                      int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                      float* dalpha, float* alpha, float* m, float* v, const bcq_adamw* opt,
+                                      void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

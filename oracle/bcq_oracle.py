@@ -280,3 +280,20 @@ def alternating_row_trace(w, q, iters=15):
     _load().orc_alternating_row_trace(_p(w), _I64(n), _INT(q), _INT(iters), _p(alpha), _p(planes), _p(err),
                                       ctypes.byref(done))
     return alpha, planes, err, int(done.value)
+
+
+def adamw_step(alpha, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """One AdamW update of the scales (Appendix A: "AdamW optimizer"; the algorithm is that of the cited AdamW
+    paper, decoupled weight decay), written out in fp64 numpy:
+        m <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2,
+        mhat = m / (1 - beta1^t),       vhat = v / (1 - beta2^t),
+        alpha <- alpha - lr * (mhat / (sqrt(vhat) + eps) + weight_decay * alpha),      t = step >= 1.
+    Returns (alpha, m, v) as new fp64 arrays; the inputs are not modified."""
+    a = np.asarray(alpha, dtype=np.float64)
+    g = np.asarray(grad, dtype=np.float64)
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    a = a - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * a)
+    return a, m, v

@@ -20,9 +20,16 @@ QUANTIZE_MAX_K = 16384
 EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_quantize", "bcq_pack",
            "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha",
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
-           "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating")
+           "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
+           "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw")
 
 _lib = None
+
+
+class AdamW(ctypes.Structure):
+    """struct bcq_adamw of include/bcq.h."""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_int64)]
 
 
 class BcqError(RuntimeError):
@@ -58,6 +65,10 @@ def load():
     lib.bcq_linear_bwd_input_grouped.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_bwd_alpha_grouped.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, i32, f32, vp, vp, sz, vp]
     lib.bcq_quantize_alternating.argtypes = [vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+    ap = ctypes.POINTER(AdamW)
+    lib.bcq_alpha_adamw_step.argtypes = [vp, vp, vp, vp, i64, ap, vp]
+    lib.bcq_linear_bwd_alpha_adamw.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, i32, f32, vp, vp, vp, vp, ap,
+                                               vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -320,5 +331,50 @@ def bcq_quantize_alternating(W, q, iters=15, g=None, alpha=None, packed=None, pl
         _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
     wp, wb = _ws(workspace)
     _check(load().bcq_quantize_alternating(_ptr(W), N, K, g, q, int(iters), _ptr(alpha), _ptr(packed),
-                                           _ptr(planes_i8), wp, wb, _stream()), "bcq_quantize_alternating")
+                                           _ptr(planes_i8), wp, wb, _stream()), "bcq_quantize_alternating",
+           "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw")
     return alpha, packed, planes_i8
+
+
+def _adamw(step, lr, beta1, beta2, eps, weight_decay):
+    return AdamW(float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), int(step))
+
+
+def bcq_alpha_adamw_step(alpha, dalpha, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """AdamW step on the first dalpha.numel() scales of `alpha` (the trained planes), in place."""
+    count = dalpha.numel()
+    for t, name in ((alpha, "alpha"), (dalpha, "dalpha"), (m, "m"), (v, "v")):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32):
+            raise ValueError("%s must be a contiguous float32 cuda tensor" % name)
+    if alpha.numel() < count or m.numel() != count or v.numel() != count:
+        raise ValueError("alpha must hold at least, and m, v exactly, dalpha.numel() elements")
+    opt = _adamw(step, lr, beta1, beta2, eps, weight_decay)
+    _check(load().bcq_alpha_adamw_step(_ptr(alpha), _ptr(dalpha), _ptr(m), _ptr(v), count, ctypes.byref(opt),
+                                       _stream()), "bcq_alpha_adamw_step")
+    return alpha
+
+
+def bcq_linear_bwd_alpha_adamw(packed, x, dy, g, alpha, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                               weight_decay=0.0, q_train=None, grad_scale=1.0, dalpha=None, workspace=None):
+    """Scale gradient + AdamW step on alpha[:q_train] in one call; returns dalpha."""
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    g = int(g)
+    dt = _act_dtype(x)
+    q_train = q if q_train is None else int(q_train)
+    G = K // max(g, 1)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(x, x.dtype, (T, K), "x")
+    _need(dy, x.dtype, (T, N), "dy")
+    _need(alpha, torch.float32, (q, N, G), "alpha")
+    _need(m, torch.float32, (q_train, N, G), "m")
+    _need(v, torch.float32, (q_train, N, G), "v")
+    dalpha = torch.empty((q_train, N, G), dtype=torch.float32, device=x.device) if dalpha is None else dalpha
+    _need(dalpha, torch.float32, (q_train, N, G), "dalpha")
+    wp, wb = _ws(workspace)
+    opt = _adamw(step, lr, beta1, beta2, eps, weight_decay)
+    _check(load().bcq_linear_bwd_alpha_adamw(_ptr(packed), _ptr(x), _ptr(dy), dt, T, N, K, g, q, q_train,
+                                             float(grad_scale), _ptr(dalpha), _ptr(alpha), _ptr(m), _ptr(v),
+                                             ctypes.byref(opt), wp, wb, _stream()), "bcq_linear_bwd_alpha_adamw")
+    return dalpha

@@ -3,6 +3,7 @@
 
 #include "bcq_internal.h"
 
+#include <math.h>
 #include <string.h>
 
 namespace {
@@ -108,7 +109,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 3; }
+int bcq_abi_version(void) { return 4; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {
@@ -266,10 +267,74 @@ bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t
                                         workspace_bytes, stream);
 }
 
+namespace {
+
+// Checks the optimizer arguments and turns them into the kernels' form.  Pure host arithmetic.
+bcq_status make_adamw(const bcq_adamw* opt, float* alpha, float* m, float* v, bcq::AdamWArgs* out) {
+    if (!opt || !alpha || !m || !v) return BCQ_ERR_NULL;
+    if (!(opt->beta1 >= 0.f && opt->beta1 < 1.f) || !(opt->beta2 >= 0.f && opt->beta2 < 1.f) || opt->step < 1 ||
+        !(opt->eps >= 0.f) || !(opt->lr == opt->lr) || !(opt->weight_decay == opt->weight_decay))
+        return BCQ_ERR_SHAPE;
+    if (misaligned(alpha) || misaligned(m) || misaligned(v)) return BCQ_ERR_ALIGN;
+    out->alpha = alpha;
+    out->m = m;
+    out->v = v;
+    out->lr = opt->lr;
+    out->beta1 = opt->beta1;
+    out->beta2 = opt->beta2;
+    out->eps = opt->eps;
+    out->weight_decay = opt->weight_decay;
+    out->inv_bc1 = (float)(1.0 / (1.0 - pow((double)opt->beta1, (double)opt->step)));
+    out->inv_bc2 = (float)(1.0 / (1.0 - pow((double)opt->beta2, (double)opt->step)));
+    return BCQ_OK;
+}
+
+bcq_status bwd_alpha_impl(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T, int64_t N,
+                          int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                          const bcq_adamw* opt, float* alpha, float* m, float* v, bool with_opt, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+}  // namespace
+
+bcq_status bcq_alpha_adamw_step(float* alpha, const float* dalpha, float* m, float* v, int64_t count,
+                                const bcq_adamw* opt, void* stream) {
+    if (!dalpha) return BCQ_ERR_NULL;
+    bcq::AdamWArgs args;
+    bcq_status s = make_adamw(opt, alpha, m, v, &args);
+    if (s != BCQ_OK) return s;
+    if (count < 1 || count > kMaxElems) return BCQ_ERR_SHAPE;
+    if (misaligned(dalpha)) return BCQ_ERR_ALIGN;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_adamw(dalpha, count, args, (hipStream_t)stream));
+}
+
+bcq_status bcq_linear_bwd_alpha_adamw(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
+                                      int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
+                                      float* dalpha, float* alpha, float* m, float* v, const bcq_adamw* opt,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_alpha_impl(packed, x, dy, dtype, T, N, K, g, q, q_train, grad_scale, dalpha, opt, alpha, m, v, true,
+                          workspace, workspace_bytes, stream);
+}
+
 bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                         int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
                                         float* dalpha, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_alpha_impl(packed, x, dy, dtype, T, N, K, g, q, q_train, grad_scale, dalpha, nullptr, nullptr, nullptr,
+                          nullptr, false, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+bcq_status bwd_alpha_impl(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T, int64_t N,
+                          int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                          const bcq_adamw* opt, float* alpha, float* m, float* v, bool with_opt, void* workspace,
+                          size_t workspace_bytes, void* stream) {
     if (!packed || !x || !dy || !dalpha) return BCQ_ERR_NULL;
+    bcq::AdamWArgs oargs = {};
+    if (with_opt && (!opt || !alpha || !m || !v)) return BCQ_ERR_NULL;
     bcq_status s = check_shape(T, N, K, q);
     if (s != BCQ_OK) return s;
     s = check_group(K, g);
@@ -277,18 +342,31 @@ bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, c
     if (q_train < 1 || q_train > q) return BCQ_ERR_SHAPE;
     if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
     if (misaligned(packed) || misaligned(x) || misaligned(dy) || misaligned(dalpha)) return BCQ_ERR_ALIGN;
+    if (with_opt) {
+        s = make_adamw(opt, alpha, m, v, &oargs);
+        if (s != BCQ_OK) return s;
+    }
     s = check_workspace(workspace, workspace_bytes, workspace_need(BCQ_OP_BWD_ALPHA, T, N, K, g, q, dtype));
     if (s != BCQ_OK) return s;
     s = check_device();
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
+    if (workspace && !small_bwd_alpha_ok(T, rowwise, dtype) && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
+        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace,
+                                               with_opt ? &oargs : nullptr, st));
+    hipError_t e;
     if (small_bwd_alpha_ok(T, rowwise, dtype))
-        return done(bcq::launch_bwd_alpha_small(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, st));
-    if (workspace && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
-        return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace, st));
-    return done(bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, g, q, q_train, grad_scale, dalpha, st));
+        e = bcq::launch_bwd_alpha_small(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, st);
+    else
+        e = bcq::launch_bwd_alpha_generic(packed, x, dy, dtype, T, N, K, g, q, q_train, grad_scale, dalpha, st);
+    if (e == hipSuccess && with_opt) e = bcq::launch_adamw(dalpha, (int64_t)q_train * N * (K / g), oargs, st);
+    return done(e);
 }
+
+}  // namespace
+
+extern "C" {
 
 bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                 int64_t N, int64_t K, int q, int q_train, float grad_scale, float* dalpha,

@@ -29,6 +29,28 @@ template <> struct Elem<bf16_t> {
     __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// ---- AdamW on the trained scales (Appendix A; decoupled weight decay) ---------------------------
+// Device pointers to the scales and their two moment buffers (fp32, same shape as the scale gradient) plus the
+// step's constants; alpha == nullptr means "no update".  inv_bc = 1 / (1 - beta^t), formed in fp64 on the host.
+struct AdamWArgs {
+    float* alpha;
+    float* m;
+    float* v;
+    float lr, beta1, beta2, eps, weight_decay, inv_bc1, inv_bc2;
+};
+
+__device__ __forceinline__ void adamw_apply(const AdamWArgs& o, int64_t idx, float g) {
+    const float m = o.beta1 * o.m[idx] + (1.f - o.beta1) * g;
+    const float v = o.beta2 * o.v[idx] + (1.f - o.beta2) * g * g;
+    o.m[idx] = m;
+    o.v[idx] = v;
+    const float a = o.alpha[idx];
+    o.alpha[idx] = a - o.lr * ((m * o.inv_bc1) / (sqrtf(v * o.inv_bc2) + o.eps) + o.weight_decay * a);
+}
+
+// alpha, m, v <- AdamW(alpha, dalpha) over `count` scales
+hipError_t launch_adamw(const float* dalpha, int64_t count, AdamWArgs args, hipStream_t st);
+
 // ---- one-time kernels -----------------------------------------------------------------------
 hipError_t launch_pack(const int8_t* planes, int64_t total_words, uint32_t* packed, hipStream_t st);
 hipError_t launch_unpack(const uint32_t* packed, int64_t total_words, int8_t* planes, hipStream_t st);
@@ -62,9 +84,10 @@ hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_
                                  int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, void* workspace,
                                  hipStream_t st);
 size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int64_t g, int q);
+// opt != nullptr: the final reduction also applies the AdamW step to the trained scales
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                  int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
-                                 void* workspace, hipStream_t st);
+                                 void* workspace, const AdamWArgs* opt, hipStream_t st);
 
 // ---- small-token kernels (bf16, at most 16 tokens per tile; plane-by-plane on the matrix cores) ----
 size_t small_bwd_input_workspace(int64_t T, int64_t N, int q);

@@ -773,7 +773,7 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 // pn = plane * N + n; `tpg` consecutive k tiles form one scale group (row-wise: all of them, G = 1).
 __global__ __launch_bounds__(256) void dalpha_reduce_kernel(const float* __restrict__ part, float* __restrict__ dalpha,
                                                             int64_t rows /* q_train * N */, int64_t G, int splits,
-                                                            int tiles_k, int tpg, float scale) {
+                                                            int tiles_k, int tpg, float scale, AdamWArgs opt) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= rows * G) return;
     const int64_t pn = idx / G, grp = idx % G;
@@ -791,12 +791,14 @@ __global__ __launch_bounds__(256) void dalpha_reduce_kernel(const float* __restr
         for (; p < tpg; ++p) s += base[(int64_t)p * rows];
     }
     dalpha[idx] = scale * s;
+    if (opt.alpha) adamw_apply(opt, idx, scale * s);
 }
 
 // Fine partials part[slice][pn][Kc] (one value per 32 columns): a group is a run of cpg consecutive values.
 __global__ __launch_bounds__(256) void dalpha_reduce_fine_kernel(const float* __restrict__ part,
                                                                  float* __restrict__ dalpha, int64_t rows, int64_t G,
-                                                                 int splits, int64_t Kc, int cpg, float scale) {
+                                                                 int splits, int64_t Kc, int cpg, float scale,
+                                                                 AdamWArgs opt) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= rows * G) return;
     const int64_t pn = idx / G, grp = idx % G;
@@ -806,6 +808,7 @@ __global__ __launch_bounds__(256) void dalpha_reduce_fine_kernel(const float* __
         for (int c = 0; c < cpg; ++c) s += base[c];
     }
     dalpha[idx] = scale * s;
+    if (opt.alpha) adamw_apply(opt, idx, scale * s);
 }
 
 struct DalphaPlan {
@@ -842,7 +845,7 @@ size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int64_t g, int 
 
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                  int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
-                                 void* workspace, hipStream_t st) {
+                                 void* workspace, const AdamWArgs* opt, hipStream_t st) {
     const int lds = 2 * DA_STAGE;
     const DalphaPlan pl = dalpha_plan(T, N, K, g, q);
     u32x4* frag = reinterpret_cast<u32x4*>(workspace);
@@ -899,12 +902,14 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     if (e != hipSuccess) return e;
     const int64_t rows = (int64_t)q_train * N, G = K / g;
     const dim3 rgrid((unsigned)((rows * G + 255) / 256));
+    AdamWArgs oa = {};
+    if (opt) oa = *opt;
     if (pl.fine)
         hipLaunchKernelGGL(dalpha_reduce_fine_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
-                           pl.splits, (int64_t)pl.tiles_k * 8, (int)(g / 32), grad_scale);
+                           pl.splits, (int64_t)pl.tiles_k * 8, (int)(g / 32), grad_scale, oa);
     else
         hipLaunchKernelGGL(dalpha_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
-                           pl.splits, pl.tiles_k, (int)(g == K ? pl.tiles_k : g / DA_TILE), grad_scale);
+                           pl.splits, pl.tiles_k, (int)(g == K ? pl.tiles_k : g / DA_TILE), grad_scale, oa);
     return hipGetLastError();
 }
 

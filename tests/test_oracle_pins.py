@@ -543,3 +543,29 @@ def test_alternating_groupwise_is_vectorwise(oracle):
     a2, b2 = oracle.quantize_alternating(W.reshape(20, 64), 3)
     assert a.shape == (3, 5, 4)
     assert np.array_equal(a.reshape(3, 20), a2) and np.array_equal(b.reshape(3, 20, 64), b2)
+
+
+# ---------------------------------------------------------------- AdamW step on the scales (Appendix A)
+
+def test_adamw_step_matches_torch_optimizer(oracle):
+    """The oracle's AdamW formula against torch.optim.AdamW (fp64, CPU) over several steps with a changing
+    learning rate (the paper's linear decay), non-zero weight decay and gradients of mixed magnitude."""
+    import torch
+    rng = _rng(90)
+    a0 = rng.uniform(0.001, 0.05, size=(2, 7, 3))
+    p = torch.nn.Parameter(torch.tensor(a0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=1e-3, betas=(0.9, 0.98), eps=1e-7, weight_decay=0.05)
+    a, m, v = a0.copy(), np.zeros_like(a0), np.zeros_like(a0)
+    for step in range(1, 6):
+        lr = 1e-3 * (1.0 - (step - 1) / 5.0)
+        g = rng.standard_normal(a0.shape) * 10.0 ** rng.integers(-4, 2)
+        for group in opt.param_groups:
+            group["lr"] = lr
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        a, m, v = oracle.adamw_step(a, g, m, v, step, lr, 0.9, 0.98, 1e-7, 0.05)
+        assert np.allclose(a, p.detach().numpy(), rtol=1e-12, atol=1e-15)
+    # first step closed form: mhat = g, vhat = g^2  ->  update = lr * (sign(g) / (1 + eps/|g|) + wd * a)
+    g = np.array([0.5, -2.0])
+    a1, _, _ = oracle.adamw_step(np.array([1.0, 1.0]), g, np.zeros(2), np.zeros(2), 1, 0.1, 0.9, 0.999, 0.0, 0.5)
+    assert np.allclose(a1, 1.0 - 0.1 * (np.sign(g) + 0.5), rtol=1e-14)
