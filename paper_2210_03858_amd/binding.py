@@ -331,8 +331,7 @@ def bcq_quantize_alternating(W, q, iters=15, g=None, alpha=None, packed=None, pl
         _need(planes_i8, torch.int8, (q, N, K), "planes_i8")
     wp, wb = _ws(workspace)
     _check(load().bcq_quantize_alternating(_ptr(W), N, K, g, q, int(iters), _ptr(alpha), _ptr(packed),
-                                           _ptr(planes_i8), wp, wb, _stream()), "bcq_quantize_alternating",
-           "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw")
+                                           _ptr(planes_i8), wp, wb, _stream()), "bcq_quantize_alternating")
     return alpha, packed, planes_i8
 
 

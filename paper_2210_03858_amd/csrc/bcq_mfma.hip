@@ -771,44 +771,59 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 
 // dalpha[pn][grp] = scale * sum over token slices and over the k tiles of group grp of part[slice][tile][pn],
 // pn = plane * N + n; `tpg` consecutive k tiles form one scale group (row-wise: all of them, G = 1).
+// A workgroup owns 64 consecutive outputs; its four waves each add a quarter of the partial sums (every fourth one,
+// eight loads in flight) and wave 0 adds the four quarters in wave order: a fixed order, bit-reproducible.
 __global__ __launch_bounds__(256) void dalpha_reduce_kernel(const float* __restrict__ part, float* __restrict__ dalpha,
                                                             int64_t rows /* q_train * N */, int64_t G, int splits,
                                                             int tiles_k, int tpg, float scale, AdamWArgs opt) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * G) return;
-    const int64_t pn = idx / G, grp = idx % G;
+    __shared__ float quarter[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t idx = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = idx < rows * G;
+    const int64_t pn = live ? idx / G : 0, grp = live ? idx % G : 0;
+    const int items = splits * tpg;  // item it = (slice it / tpg, tile it % tpg of the group)
     float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) {
-        const float* base = part + ((int64_t)sp * tiles_k + grp * tpg) * rows + pn;
-        int p = 0;
-        for (; p + 8 <= tpg; p += 8) {  // eight independent loads in flight, added in index order
-            float v[8];
+    int it = wave;
+    for (; it + 28 < items; it += 32) {
+        float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = base[(int64_t)(p + u) * rows];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) s += v[u];
+        for (int u = 0; u < 8; ++u) {
+            const int iu = it + 4 * u;
+            v[u] = part[((int64_t)(iu / tpg) * tiles_k + grp * tpg + iu % tpg) * rows + pn];
         }
-        for (; p < tpg; ++p) s += base[(int64_t)p * rows];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
     }
-    dalpha[idx] = scale * s;
-    if (opt.alpha) adamw_apply(opt, idx, scale * s);
+    for (; it < items; it += 4) s += part[((int64_t)(it / tpg) * tiles_k + grp * tpg + it % tpg) * rows + pn];
+    quarter[wave][lane] = s;
+    __syncthreads();
+    if (wave != 0 || !live) return;
+    const float total = scale * ((quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]));
+    dalpha[idx] = total;
+    if (opt.alpha) adamw_apply(opt, idx, total);
 }
 
 // Fine partials part[slice][pn][Kc] (one value per 32 columns): a group is a run of cpg consecutive values.
+// Same split of the work as above: item it = (slice it / cpg, value it % cpg of the run).
 __global__ __launch_bounds__(256) void dalpha_reduce_fine_kernel(const float* __restrict__ part,
                                                                  float* __restrict__ dalpha, int64_t rows, int64_t G,
                                                                  int splits, int64_t Kc, int cpg, float scale,
                                                                  AdamWArgs opt) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * G) return;
-    const int64_t pn = idx / G, grp = idx % G;
+    __shared__ float quarter[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t idx = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = idx < rows * G;
+    const int64_t pn = live ? idx / G : 0, grp = live ? idx % G : 0;
+    const int items = splits * cpg;
     float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) {
-        const float* base = part + ((int64_t)sp * rows + pn) * Kc + grp * cpg;
-        for (int c = 0; c < cpg; ++c) s += base[c];
-    }
-    dalpha[idx] = scale * s;
-    if (opt.alpha) adamw_apply(opt, idx, scale * s);
+    for (int it = wave; it < items; it += 4)
+        s += part[((int64_t)(it / cpg) * rows + pn) * Kc + grp * cpg + it % cpg];
+    quarter[wave][lane] = s;
+    __syncthreads();
+    if (wave != 0 || !live) return;
+    const float total = scale * ((quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]));
+    dalpha[idx] = total;
+    if (opt.alpha) adamw_apply(opt, idx, total);
 }
 
 struct DalphaPlan {
@@ -901,7 +916,7 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t rows = (int64_t)q_train * N, G = K / g;
-    const dim3 rgrid((unsigned)((rows * G + 255) / 256));
+    const dim3 rgrid((unsigned)((rows * G + 63) / 64));
     AdamWArgs oa = {};
     if (opt) oa = *opt;
     if (pl.fine)
