@@ -81,11 +81,14 @@ size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q,
     const bool rowwise = (g == K);
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
-        case BCQ_OP_FWD: return mfma_fwd_ok(T, rowwise, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
+        case BCQ_OP_FWD:
+            if (small_fwd_ok(T, rowwise, dtype)) return bcq::stream_fwd_workspace(T, K);
+            return mfma_fwd_ok(T, rowwise, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
         case BCQ_OP_BWD_INPUT:
-            if (small_bwd_input_ok(T, N, rowwise, dtype)) return bcq::small_bwd_input_workspace(T, N, q);
+            if (small_bwd_input_ok(T, N, rowwise, dtype)) return bcq::stream_bwd_input_workspace(T, N, q);
             return mfma_bwd_input_ok(T, N, rowwise, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
         case BCQ_OP_BWD_ALPHA:
+            if (small_bwd_alpha_ok(T, rowwise, dtype)) return bcq::stream_bwd_alpha_workspace(T, K);
             return mfma_bwd_alpha_ok(T, N, K, rowwise, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, g, q) : 0;
         default: return 0;
     }
@@ -223,7 +226,10 @@ bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, co
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
-    if (small_fwd_ok(T, rowwise, dtype)) return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, st));
+    if (small_fwd_ok(T, rowwise, dtype)) {
+        if (workspace) return done(bcq::launch_fwd_stream(packed, alpha, x, T, N, K, q, y, workspace, st));
+        return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, st));
+    }
     if (workspace && mfma_fwd_ok(T, rowwise, dtype))
         return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, g, q, y, workspace, st));
     return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, g, q, y, st));
@@ -254,7 +260,7 @@ bcq_status bcq_linear_bwd_input_grouped(const uint32_t* packed, const uint32_t* 
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
     if (workspace && packed_t && small_bwd_input_ok(T, N, rowwise, dtype))
-        return done(bcq::launch_bwd_input_small(packed_t, alpha, dy, T, N, K, q, dx, workspace, st));
+        return done(bcq::launch_bwd_input_stream(packed_t, alpha, dy, T, N, K, q, dx, workspace, st));
     if (workspace && mfma_bwd_input_ok(T, N, rowwise, dtype))
         return done(bcq::launch_bwd_input_mfma(packed, packed_t, alpha, dy, T, N, K, g, q, dx, workspace, st));
     return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, g, q, dx, st));
@@ -352,6 +358,11 @@ bcq_status bwd_alpha_impl(const uint32_t* packed, const void* x, const void* dy,
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
+    if (workspace && small_bwd_alpha_ok(T, rowwise, dtype)) {
+        hipError_t e = bcq::launch_bwd_alpha_stream(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, workspace, st);
+        if (e == hipSuccess && with_opt) e = bcq::launch_adamw(dalpha, (int64_t)q_train * N * (K / g), oargs, st);
+        return done(e);
+    }
     if (workspace && !small_bwd_alpha_ok(T, rowwise, dtype) && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
         return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace,
                                                with_opt ? &oargs : nullptr, st));

@@ -1,0 +1,491 @@
+// Small-token path on the block-scaled FP4 x FP8 matrix instruction of gfx950 (up to 16 tokens per tile, bf16 I/O,
+// row-wise scales).  It evaluates AlphaTuning Eq. 2 / Eq. 4 / Eq. 3 plane by plane, as they are written,
+//     y[t][n]     = sum_i alpha_i[n] * C_i[n][t]          C_i[n][t] = sum_k B_i[n][k] x[t][k]          (Eq. 2)
+//     dalpha_i[n] = s * sum_t dy[t][n] * C_i[n][t]                                                      (Eq. 4)
+//     dx[t][k]    = sum_i sum_n B_i[n][k] * (alpha_i[n] dy[t][n])                                       (Eq. 3)
+// streaming the packed sign planes from HBM exactly once.  What matters here is the work per weight BIT:
+//   * v_mfma_scale_f32_16x16x128_f8f6f4 takes the signs as FP4 (e2m1) codes: +1 = 0x2, -1 = 0xA.  One packed word
+//     (32 signs) becomes the 4 operand registers of a lane with one shift and one three-input bit operation each:
+//         reg_s = ((word << s) & 0x88888888) ^ 0xAAAAAAAA,  s = 0..3
+//     (nibble jj of reg_s carries bit 4 jj + 3 - s of the word) - 8 vector-ALU operations per 32 weights.
+//   * The activations are the other operand as FP8 (e4m3) with a power-of-two scale per 32 contraction indices
+//     (hardware block scaling).  A bf16 value has 8 significant bits = two e4m3 terms of 4 bits each, so
+//     x = s (f1 + f2 / 16) EXACTLY for every element within 2^-13 of its block's maximum (smaller elements keep an
+//     absolute error below 2^-21 of that maximum).  A short pre-kernel writes the two terms, already in the
+//     register order of the instruction and with the contraction index permuted to match the sign expansion
+//     above.  With at most 8 tokens both terms sit side by side in the 16 columns of ONE instruction
+//     (column t and t + 8), else they take two instructions.
+// Measured on this part: 15.3 ns per instruction per SIMD for 16 x 16 x 128, i.e. 4.4x the contraction length per
+// nanosecond of the bf16 16x16x32 form the other small-token kernel uses.
+//
+// Operand layout of the instruction (found by register-only probes and used below): hardware contraction index
+// kappa in [0, 128), chunk c = kappa / 16.  FP4 operand: lane (row, g) holds kappa = 32 g .. 32 g + 31 as nibbles
+// 0 .. 31 of its four registers.  FP8 operand: lane (col, g) holds chunks g and g + 4 in bytes 0 .. 15 and
+// 16 .. 31 of its eight registers.  The scale byte of lane (col, g) multiplies kappa = 32 g .. 32 g + 31.
+// Result register v of lane l: row 4 (l / 16) + v, column l % 16.
+//
+// Work split as in the other small-token kernel: a workgroup owns 16 R rows of the plane matrix and one 16-token
+// tile; its waves split the 512-column segments and add their tiles through LDS in wave order (deterministic).
+#include "bcq_internal.h"
+
+namespace bcq {
+
+typedef __attribute__((ext_vector_type(8))) int q_i32x8;
+typedef __attribute__((ext_vector_type(4))) float q_f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t q_u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t q_u32x2;
+typedef __attribute__((ext_vector_type(2))) float q_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 q_bf16x2;
+
+enum { STREAM_FWD = 0, STREAM_DALPHA = 1, STREAM_DX = 2 };
+
+constexpr int QBLK = 2048;   // bytes of one FP8 operand: 64 lanes x 32 B
+constexpr int QSCL = 256;    // bytes of the scales of one segment and half: 64 lanes x 4 instructions
+
+struct StreamPlan {
+    int R, W, segs_per_wave, halves, tiles;
+    int64_t segs;
+    unsigned grid_x;
+    size_t xq_bytes, sq_bytes;  // per plane set (DX has q of them)
+};
+
+__device__ __forceinline__ uint32_t q_pack_bf16x2(float lo, float hi) {
+    q_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, q_bf16x2));
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Pre-kernel: activations -> two block-scaled FP8 terms in operand order.
+// One thread per (token tile, segment, instruction j, token, 32-index block G): it owns packed-word position
+// 16 seg + 4 G + j of the contraction axis (32 columns), finds the block's power-of-two scale, and writes
+// 2 x 16 bytes per term plus the scale bytes.  DX: the activation is dy[t][n] * alpha_i[n] for plane i = blockIdx.y.
+template <int MODE>
+__global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict__ act, const float* __restrict__ alpha,
+                                                        int64_t T, int64_t C, int64_t segs, int halves, int tiles,
+                                                        unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
+                                                        size_t xq_plane, size_t sq_plane) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
+    const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
+    if (tile >= tiles) return;
+    const int plane = blockIdx.y;
+    xq += (size_t)plane * xq_plane;
+    sq += (size_t)plane * sq_plane;
+    const int64_t t = tile * 16 + tl;
+    const bool one_half = (halves == 1);
+    const int64_t word = seg * 16 + 4 * G + j;  // 32 columns of the contraction axis
+    const bool live = (t < T) && (word * 32 < C) && (!one_half || tl < 8);
+    float v[32];
+    if (live) {
+        const q_u32x4* src = reinterpret_cast<const q_u32x4*>(act + t * C + word * 32);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const q_u32x4 r = src[b];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[8 * b + 2 * e] = __uint_as_float(r[e] << 16);
+                v[8 * b + 2 * e + 1] = __uint_as_float(r[e] & 0xFFFF0000u);
+            }
+        }
+        if (MODE == STREAM_DX) {
+            const float* a = alpha + (int64_t)plane * C + word * 32;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] *= a[e];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 32; ++e) v[e] = 0.f;
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
+    // smallest power of two 2^E with amax / 2^E <= 448 (largest e4m3 value = 1.75 * 2^8); scale byte = E + 127
+    int sb1 = 127;
+    if (amax > 0.f && amax <= 3.0e38f) {
+        const uint32_t u = __float_as_uint(amax);
+        const int e = (int)(u >> 23) - 127;
+        const int E = ((u & 0x7FFFFFu) <= 0x600000u) ? e - 8 : e - 7;
+        sb1 = E + 127;
+        sb1 = sb1 < 0 ? 0 : sb1;
+    }
+    const int sb2 = sb1 >= 4 ? sb1 - 4 : 0;                       // second term: 1/16 of the first scale
+    const float inv1 = __uint_as_float((uint32_t)(254 - sb1) << 23); // 2^-(sb1 - 127); sb1 <= 247, so it is normal
+    const float up2 = __uint_as_float((uint32_t)(127 + sb1 - sb2) << 23);
+    // element kappa' = 8 s + jj of the block is bit (column) 4 jj + 3 - s of the word
+    uint32_t t1[8], t2[8];
+#pragma unroll
+    for (int pr = 0; pr < 16; ++pr) {
+        const int k0 = 2 * pr, k1 = 2 * pr + 1;
+        const float x0 = v[4 * (k0 & 7) + 3 - (k0 >> 3)] * inv1, x1 = v[4 * (k1 & 7) + 3 - (k1 >> 3)] * inv1;
+        const int p1 = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+        const q_f32x2 d = __builtin_amdgcn_cvt_pk_f32_fp8(p1, false);
+        const int p2 = __builtin_amdgcn_cvt_pk_fp8_f32((x0 - d[0]) * up2, (x1 - d[1]) * up2, 0, false);
+        if ((pr & 1) == 0) {
+            t1[pr >> 1] = (uint32_t)p1 & 0xFFFFu;
+            t2[pr >> 1] = (uint32_t)p2 & 0xFFFFu;
+        } else {
+            t1[pr >> 1] |= (uint32_t)p1 << 16;
+            t2[pr >> 1] |= (uint32_t)p2 << 16;
+        }
+    }
+    // chunk 2 G + cc (cc = 0, 1) lives in lane group (2 G + cc) % 4, bytes 16 ((2 G + cc) / 4) .. + 15
+    const int col1 = tl, col2 = one_half ? tl + 8 : tl;
+    const int half2 = one_half ? 0 : 1;
+    if (one_half && tl >= 8) return;  // columns 8 .. 15 of the single half belong to the second term of tokens 0 .. 7
+    const size_t blk = ((size_t)(tile * segs + seg) * 4 + j) * halves;
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+        const int c = 2 * G + cc, gB = c & 3, hh = c >> 2;
+        const q_u32x4 o1 = {t1[4 * cc], t1[4 * cc + 1], t1[4 * cc + 2], t1[4 * cc + 3]};
+        const q_u32x4 o2 = {t2[4 * cc], t2[4 * cc + 1], t2[4 * cc + 2], t2[4 * cc + 3]};
+        *reinterpret_cast<q_u32x4*>(xq + (blk + 0) * QBLK + (gB * 16 + col1) * 32 + 16 * hh) = o1;
+        *reinterpret_cast<q_u32x4*>(xq + (blk + half2) * QBLK + (gB * 16 + col2) * 32 + 16 * hh) = o2;
+    }
+    const size_t sblk = (size_t)(tile * segs + seg) * halves;
+    sq[(sblk + 0) * QSCL + (col1 + 16 * G) * 4 + j] = (unsigned char)sb1;
+    sq[(sblk + half2) * QSCL + (col2 + 16 * G) * 4 + j] = (unsigned char)sb2;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// planes: [q][rows][cw] words (canonical for FWD / DALPHA, twin for DX); xq / sq: output of quant_act_kernel
+// (DX: one set per plane).  rows x 32 cw is the plane matrix seen by this kernel.
+template <int MODE, int R, int QP, bool TWO>
+__global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict__ planes,
+                                                      const unsigned char* __restrict__ xq,
+                                                      const unsigned char* __restrict__ sq,
+                                                      const float* __restrict__ alpha, const bf16_t* __restrict__ dy,
+                                                      void* __restrict__ out, int64_t T, int64_t rows, int64_t cw,
+                                                      int q_used, float scale, int segs_per_wave, int64_t segs,
+                                                      size_t xq_plane, size_t sq_plane, int scale_a) {
+    extern __shared__ __attribute__((aligned(16))) float red[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int rl = lane & 15, g = lane >> 4;
+    const int64_t row0 = (int64_t)blockIdx.x * 16 * R;
+    const int64_t tile = blockIdx.y;
+    const int64_t t0 = tile * 16;
+    constexpr int H = TWO ? 2 : 1;
+    constexpr int NACC = (MODE == STREAM_DX) ? 1 : QP;
+    constexpr int PPP = QP;  // planes handled per segment (DX: q_used real planes, the rest repeat the last)
+
+    q_f32x4 acc[R][NACC];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) acc[r][i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint32_t* prow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t rr = row0 + 16 * r + rl;
+        rr = rr < rows ? rr : rows - 1;  // rows beyond the matrix give outputs that are never stored
+        prow[r] = planes + rr * cw;
+    }
+    const int64_t plane_stride = rows * cw;
+
+    // result column of this lane -> token: with one half, columns t and t + 8 both belong to token t
+    const int tcol = TWO ? rl : (rl & 7);
+    const bool tok_live = (t0 + tcol) < T;
+    const int64_t tok = tok_live ? t0 + tcol : T - 1;
+
+    float ep[R][QP][4];  // FWD: alpha_i of this lane's 4 rows; DALPHA: dy of this lane's token and 4 rows (slot 0)
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            int64_t n = row0 + 16 * r + 4 * g + v;
+            const bool n_live = n < rows;
+            n = n_live ? n : rows - 1;
+            if (MODE == STREAM_FWD) {
+#pragma unroll
+                for (int i = 0; i < QP; ++i) ep[r][i][v] = (i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+            } else if (MODE == STREAM_DALPHA) {
+                ep[r][0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
+            }
+        }
+
+    const int seg_begin = wave * segs_per_wave;
+    const unsigned char* xq_t = xq + (size_t)tile * segs * 4 * H * QBLK + (size_t)lane * 32;
+    const unsigned char* sq_t = sq + (size_t)tile * segs * H * QSCL + (size_t)lane * 4;
+
+    for (int s = 0; s < segs_per_wave; ++s) {
+        const int64_t seg = seg_begin + s;
+        if (seg >= segs) break;  // whole wave leaves together
+        const int64_t w0 = seg * 16 + 4 * g;
+        const bool quad = (w0 + 3 < cw) && ((cw & 3) == 0);
+        uint32_t bits[R][PPP][4];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < PPP; ++i) {
+                const int ic = i < q_used ? i : q_used - 1;
+                const uint32_t* pr = prow[r] + (int64_t)ic * plane_stride;
+                if (quad) {
+                    const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(pr + w0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) bits[r][i][j] = v4[j];
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int64_t wj = (w0 + j) < cw ? w0 + j : cw - 1;  // columns beyond C meet zero activations
+                        bits[r][i][j] = pr[wj];
+                    }
+                }
+            }
+        constexpr int NSET = (MODE == STREAM_DX) ? PPP : 1;  // DX: every plane has its own scaled activations
+        int sc[NSET][H];
+#pragma unroll
+        for (int ps = 0; ps < NSET; ++ps) {
+            const int pc = ps < q_used ? ps : q_used - 1;
+#pragma unroll
+            for (int h = 0; h < H; ++h)
+                sc[ps][h] = *reinterpret_cast<const int*>(sq_t + (size_t)pc * sq_plane + ((size_t)seg * H + h) * QSCL);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            q_i32x8 bop[NSET][H];
+#pragma unroll
+            for (int ps = 0; ps < NSET; ++ps) {
+                const int pc = ps < q_used ? ps : q_used - 1;
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    const q_u32x4* bp = reinterpret_cast<const q_u32x4*>(xq_t + (size_t)pc * xq_plane +
+                                                                         (((size_t)seg * 4 + j) * H + h) * QBLK);
+                    const q_u32x4 lo = bp[0], hi = bp[1];
+                    bop[ps][h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
+                                         (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < PPP; ++i) {
+                    const uint32_t wd = bits[r][i][j];
+                    q_i32x8 aop;
+#pragma unroll
+                    for (int sft = 0; sft < 4; ++sft) aop[sft] = (int)(((wd << sft) & 0x88888888u) ^ 0xAAAAAAAAu);
+                    aop[4] = 0;
+                    aop[5] = 0;
+                    aop[6] = 0;
+                    aop[7] = 0;
+                    constexpr int DXI = (MODE == STREAM_DX) ? 1 : 0;
+                    const int ai = DXI ? 0 : i;
+                    const int ps = DXI ? i : 0;
+                    if (MODE == STREAM_DX && i >= q_used) continue;  // uniform: planes beyond q do not exist
+#pragma unroll
+                    for (int h = 0; h < H; ++h) {
+                        // the instruction picks byte j of the scale register (its op_sel), so j must be a constant
+                        if (j == 0)
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 0, sc[ps][h]);
+                        else if (j == 1)
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 1, sc[ps][h]);
+                        else if (j == 2)
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 2, sc[ps][h]);
+                        else
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 3, sc[ps][h]);
+                    }
+                }
+        }
+    }
+
+    // one half: add the second term's columns (t + 8) onto the first term's (t); lanes l and l ^ 8 swap
+    if (!TWO) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < NACC; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[r][i][v] += __shfl_xor(acc[r][i][v], 8);
+    }
+
+    // From here on as in the bf16 small-token kernel.  Result register v of lane l: row 4 (l / 16) + v, token column.
+    constexpr int NOUT = (MODE == STREAM_DALPHA) ? QP : 1;
+    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
+    q_f32x4 part[R][NOUT];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (MODE == STREAM_FWD) {
+            q_f32x4 y = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < QP; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) y[v] += ep[r][i][v] * acc[r][i][v];  // alpha of unused planes is 0
+            part[r][0] = y;
+        } else if (MODE == STREAM_DX) {
+            part[r][0] = acc[r][0];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NOUT; ++i) part[r][i] = acc[r][i < NACC ? i : 0];
+        }
+    }
+    if (W > 1) {  // cross-wave sum in wave order: red[w][r][o][lane][4]
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int o = 0; o < NOUT; ++o)
+                if (o < nout) *reinterpret_cast<q_f32x4*>(&red[(((wave * R + r) * nout + o) * 64 + lane) * 4]) = part[r][o];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int o = 0; o < NOUT; ++o)
+                if (o < nout) {
+                    q_f32x4 sum = part[r][o];
+                    for (int w = 1; w < W; ++w) sum += *reinterpret_cast<const q_f32x4*>(&red[(((w * R + r) * nout + o) * 64 + lane) * 4]);
+                    part[r][o] = sum;
+                }
+    }
+    const bool col_live = tok_live && (TWO || rl < 8);  // with one half, columns 8 .. 15 duplicate columns 0 .. 7
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t n = row0 + 16 * r + 4 * g;  // first of this lane's 4 rows
+        if (MODE == STREAM_DALPHA) {
+#pragma unroll
+            for (int o = 0; o < NOUT; ++o)
+                if (o < nout) {
+                    q_f32x4 sum;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float x = col_live ? ep[r][0][v] * part[r][o][v] : 0.f;
+                        x += __shfl_xor(x, 1);
+                        x += __shfl_xor(x, 2);
+                        x += __shfl_xor(x, 4);
+                        x += __shfl_xor(x, 8);
+                        sum[v] = x * scale;
+                    }
+                    if (rl == 0)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (n + v < rows) reinterpret_cast<float*>(out)[(int64_t)o * rows + n + v] = sum[v];
+                }
+        } else {
+            bf16_t* o = reinterpret_cast<bf16_t*>(out);
+            if (col_live) {
+                if (n + 3 < rows && (rows & 3) == 0) {
+                    q_u32x2 pk;
+                    pk[0] = q_pack_bf16x2(part[r][0][0], part[r][0][1]);
+                    pk[1] = q_pack_bf16x2(part[r][0][2], part[r][0][3]);
+                    *reinterpret_cast<q_u32x2*>(o + tok * rows + n) = pk;
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (n + v < rows) o[tok * rows + n + v] = f32_to_bf16(part[r][0][v]);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw) {
+    StreamPlan p;
+    p.segs = (cw + 15) / 16;
+    p.halves = T <= 8 ? 1 : 2;
+    p.tiles = (int)((T + 15) / 16);
+    p.R = rows >= 16384 ? 2 : 1;
+    const int64_t blocks = (rows + 16 * p.R - 1) / (16 * p.R);
+    // waves per workgroup: aim at about two waves per SIMD (2048 on the chip); among the candidates from there up to
+    // 8 take the first that keeps every wave at least 80 % loaded, else the best balanced
+    const int wmax = (int)(p.segs < 8 ? p.segs : 8);
+    int w0 = (int)((2048 + blocks - 1) / blocks);
+    w0 = w0 < 1 ? 1 : (w0 > wmax ? wmax : w0);
+    int best_w = w0;
+    double best_eff = 0.0;
+    for (int w = w0; w <= wmax; ++w) {
+        const int64_t spw = (p.segs + w - 1) / w;
+        const double eff = (double)p.segs / (double)(w * spw);
+        if (eff >= 0.8) {
+            best_w = w;
+            break;
+        }
+        if (eff > best_eff + 1e-9) {
+            best_eff = eff;
+            best_w = w;
+        }
+    }
+    p.W = best_w;
+    p.segs_per_wave = (int)((p.segs + best_w - 1) / best_w);
+    p.grid_x = (unsigned)blocks;
+    p.xq_bytes = (size_t)p.tiles * p.segs * 4 * p.halves * QBLK;
+    p.sq_bytes = (size_t)p.tiles * p.segs * p.halves * QSCL;
+    return p;
+}
+
+size_t stream_workspace(int64_t T, int64_t contraction, int sets) {
+    const StreamPlan p = stream_plan(T, 16, contraction / 32);
+    return (size_t)sets * (p.xq_bytes + p.sq_bytes);
+}
+
+template <int MODE>
+static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
+                                int64_t T, int64_t rows, int64_t cw, int q, int q_used, float scale, void* workspace,
+                                hipStream_t st) {
+    const StreamPlan p = stream_plan(T, rows, cw);
+    if (p.W < 1 || p.W > 8) return hipErrorInvalidConfiguration;  // the kernel is compiled for at most 512 threads
+    const int sets = (MODE == STREAM_DX) ? q : 1;
+    unsigned char* xq = reinterpret_cast<unsigned char*>(workspace);
+    unsigned char* sq = xq + (size_t)sets * p.xq_bytes;
+    {
+        const int64_t threads = (int64_t)p.tiles * p.segs * 256;
+        const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)sets);
+        hipLaunchKernelGGL((quant_act_kernel<MODE>), grid, dim3(256), 0, st, act, alpha, T, cw * 32, p.segs, p.halves,
+                           p.tiles, xq, sq, p.xq_bytes, p.sq_bytes);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid(p.grid_x, (unsigned)p.tiles);
+    const dim3 block((unsigned)(64 * p.W));
+    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
+    const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
+    const int qp = q_used <= 4 ? q_used : 8;
+#define BCQ_STREAM_LAUNCH(RR, QQ, TT)                                                                                  \
+    hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, rows,   \
+                       cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127)
+#define BCQ_STREAM_Q(RR, TT)                                      \
+    switch (qp) {                                                 \
+        case 1: BCQ_STREAM_LAUNCH(RR, 1, TT); break;              \
+        case 2: BCQ_STREAM_LAUNCH(RR, 2, TT); break;              \
+        case 3: BCQ_STREAM_LAUNCH(RR, 3, TT); break;              \
+        case 4: BCQ_STREAM_LAUNCH(RR, 4, TT); break;              \
+        default: BCQ_STREAM_LAUNCH(RR, 8, TT); break;             \
+    }
+    if (p.halves == 2) {
+        if (p.R == 2) {
+            BCQ_STREAM_Q(2, true)
+        } else {
+            BCQ_STREAM_Q(1, true)
+        }
+    } else {
+        if (p.R == 2) {
+            BCQ_STREAM_Q(2, false)
+        } else {
+            BCQ_STREAM_Q(1, false)
+        }
+    }
+#undef BCQ_STREAM_Q
+#undef BCQ_STREAM_LAUNCH
+    return hipGetLastError();
+}
+
+size_t stream_fwd_workspace(int64_t T, int64_t K) { return stream_workspace(T, K, 1); }
+size_t stream_bwd_alpha_workspace(int64_t T, int64_t K) { return stream_workspace(T, K, 1); }
+size_t stream_bwd_input_workspace(int64_t T, int64_t N, int q) { return stream_workspace(T, N, q); }
+
+hipError_t launch_fwd_stream(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
+                             int64_t K, int q, void* y, void* workspace, hipStream_t st) {
+    return launch_stream<STREAM_FWD>(packed, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, workspace, st);
+}
+
+hipError_t launch_bwd_alpha_stream(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
+                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
+                                   hipStream_t st) {
+    return launch_stream<STREAM_DALPHA>(packed, (const bf16_t*)x, nullptr, (const bf16_t*)dy, dalpha, T, N, K / 32, q,
+                                        q_train, grad_scale, workspace, st);
+}
+
+hipError_t launch_bwd_input_stream(const uint32_t* packed_t, const float* alpha, const void* dy, int64_t T, int64_t N,
+                                   int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
+    return launch_stream<STREAM_DX>(packed_t, (const bf16_t*)dy, alpha, nullptr, dx, T, K, N / 32, q, q, 1.f, workspace, st);
+}
+
+}  // namespace bcq
