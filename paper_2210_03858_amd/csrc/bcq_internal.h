@@ -89,14 +89,11 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
                                  int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
                                  void* workspace, const AdamWArgs* opt, hipStream_t st);
 
-// ---- small-token kernels (bf16, at most 16 tokens per tile; plane-by-plane on the matrix cores) ----
-size_t small_bwd_input_workspace(int64_t T, int64_t N, int q);
+// ---- small-token kernels without workspace (bf16, at most 16 tokens per tile; plane-by-plane, bf16 MFMA) ----
 hipError_t launch_fwd_small(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
                             int64_t K, int q, void* y, hipStream_t st);
 hipError_t launch_bwd_alpha_small(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, hipStream_t st);
-hipError_t launch_bwd_input_small(const uint32_t* packed_t, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                  int64_t K, int q, void* dx, void* workspace, hipStream_t st);
 
 // ---- small-token kernels on the block-scaled FP4 x FP8 matrix instruction (bf16, row-wise scales; need a
 // workspace for the activations re-coded as two FP8 terms) ----

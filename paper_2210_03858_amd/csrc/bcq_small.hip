@@ -1,8 +1,9 @@
-// Small-token path (up to 16 tokens per pass, bf16): streams the packed sign planes from HBM exactly once and
-// feeds them to the matrix cores plane by plane, as AlphaTuning Eq. 2 is written:
+// Small-token path without a workspace (up to 16 tokens per pass, bf16, forward and scale gradient): streams the
+// packed sign planes from HBM exactly once and feeds them to the matrix cores plane by plane, as AlphaTuning
+// Eq. 2 is written:
 //     y[t][n]      = sum_i alpha_i[n] * C_i[n][t]           C_i[n][t] = sum_k B_i[n][k] x[t][k]      (Eq. 2)
 //     dalpha_i[n]  = s * sum_t dy[t][n] * C_i[n][t]                                                    (Eq. 4)
-//     dx[t][k]     = sum_i sum_n B_i[n][k] * (alpha_i[n] dy[t][n])                                     (Eq. 3)
+// (With a workspace the library uses the FP4 x FP8 kernels of bcq_stream.hip instead, which also cover Eq. 3.)
 // In this regime the work per weight BIT is what matters (the planes are the only large operand), so nothing
 // is dequantised: a lane turns 8 sign bits into 8 bf16 values of +-1 with 8 vector-ALU operations (one shift
 // and one three-input bit operation per register pair) and v_mfma_f32_16x16x32_bf16 multiplies them with a
@@ -14,9 +15,6 @@
 // bytes of a row), so a plane word is fetched by exactly one lane of one wave.  The contraction index is permuted inside the MFMA (lane group g owns columns
 // 128 g .. 128 g + 127 of a 512-column segment, and a register pair holds columns c and c + 16 of a word) - legal because
 // both operands use the same permutation - which is what makes the one-shift expansion possible.
-//
-// The input gradient uses the transposed twin (rows = columns k of W, bits along n) and activations
-// pre-multiplied per plane, dy * alpha_i, rounded to bf16 by a small pre-kernel into the workspace.
 #include "bcq_internal.h"
 
 namespace bcq {
@@ -28,7 +26,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t s_u32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 s_bf16x2;
 typedef __attribute__((ext_vector_type(2))) float s_f32x2;
 
-enum { SMALL_FWD = 0, SMALL_DALPHA = 1, SMALL_DX = 2 };
+enum { SMALL_FWD = 0, SMALL_DALPHA = 1 };
 
 __device__ __forceinline__ uint32_t s_pack_bf16x2(float lo, float hi) {
     s_f32x2 v = {lo, hi};
@@ -60,8 +58,7 @@ __device__ __forceinline__ s_bf16x8 load_act_frag(const bf16_t* p32, int u, bool
     return __builtin_bit_cast(s_bf16x8, r);
 }
 
-// planes: [q][rows][cw] words (canonical for FWD / DALPHA, twin for DX).  act: FWD, DALPHA: x[T][C];
-// DX: scaled activations [q][T][C].  rows x C is the plane matrix seen by this kernel (C = 32 cw).
+// planes: [q][rows][cw] words (canonical layout); act: x[T][C].  rows x C is the plane matrix (C = 32 cw).
 template <int MODE, int R, int QP>
 __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__ planes, const bf16_t* __restrict__ act,
                                                      const float* __restrict__ alpha, const bf16_t* __restrict__ dy,
@@ -75,7 +72,7 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
     const int64_t C = cw * 32;
     const bool tok_live = (t0 + rl) < T;
     const int64_t tok = tok_live ? t0 + rl : T - 1;
-    constexpr int NACC = (MODE == SMALL_DX) ? 1 : QP;  // planes beyond q_used read plane q_used-1 again and are dropped
+    constexpr int NACC = QP;  // planes beyond q_used read plane q_used-1 again and are dropped
 
     s_f32x4 acc[R][NACC];
 #pragma unroll
@@ -132,11 +129,10 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
     };
 
     const int seg_begin = wave * segs_per_wave;
-    const int npass = (MODE == SMALL_DX) ? q_used : 1;
-    constexpr int PPP = (MODE == SMALL_DX) ? 1 : QP;          // planes per pass; DX: one pass per plane
-    for (int pass = 0; pass < npass; ++pass) {
-        const bf16_t* act_row = act + ((int64_t)pass * T + tok) * C;  // pass = plane for DX, 0 otherwise
-        const uint32_t* pbase = planes + (int64_t)pass * ((MODE == SMALL_DX) ? plane_stride : 0);
+    constexpr int PPP = QP;  // planes per pass
+    {
+        const bf16_t* act_row = act + tok * C;
+        const uint32_t* pbase = planes;
         for (int s = 0; s < segs_per_wave; ++s) {
             if ((int64_t)(seg_begin + s) * 16 >= cw) break;                // whole wave leaves together
             const int64_t w0 = ((int64_t)(seg_begin + s) * 16) + 4 * g;  // first of this lane's four words
@@ -154,7 +150,7 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int i = 0; i < PPP; ++i) {
-                    const int ic = (MODE == SMALL_DX || i < q_used) ? i : q_used - 1;
+                    const int ic = i < q_used ? i : q_used - 1;
                     const uint32_t* pr = pbase + (prow[r] - planes) + (int64_t)ic * plane_stride;
                     if (quad) {
                         const s_u32x4 v4 = *reinterpret_cast<const s_u32x4*>(pr + w0);
@@ -214,8 +210,6 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
 #pragma unroll
                 for (int v = 0; v < 4; ++v) y[v] += ep[r][i][v] * acc[r][i][v];  // alpha of unused planes is 0
             part[r][0] = y;
-        } else if (MODE == SMALL_DX) {
-            part[r][0] = acc[r][0];
         } else {
 #pragma unroll
             for (int i = 0; i < NOUT; ++i) part[r][i] = acc[r][i < NACC ? i : 0];
@@ -285,16 +279,6 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
     }
 }
 
-// dys[i][t][n] = bf16(dy[t][n] * alpha_i[n])
-__global__ __launch_bounds__(256) void scale_dy_kernel(const bf16_t* __restrict__ dy, const float* __restrict__ alpha,
-                                                       bf16_t* __restrict__ dys, int64_t T, int64_t N, int q) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= T * N) return;
-    const int64_t n = idx % N;
-    const float d = bf16_to_f32(dy[idx]);
-    for (int i = 0; i < q; ++i) dys[(int64_t)i * T * N + idx] = f32_to_bf16(d * alpha[(int64_t)i * N + n]);
-}
-
 struct SmallPlan {
     int R, W, segs_per_wave;
     unsigned grid_x;
@@ -339,7 +323,7 @@ static hipError_t launch_small(const uint32_t* planes, const bf16_t* act, const 
     if (p.W < 1 || p.W > 8) return hipErrorInvalidConfiguration;  // the kernel is compiled for at most 512 threads
     const int nout = (MODE == SMALL_DALPHA) ? q_used : 1;
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
-    const int qp = (MODE == SMALL_DX) ? 1 : (q_used <= 4 ? q_used : 8);
+    const int qp = q_used <= 4 ? q_used : 8;
 #define BCQ_SMALL_LAUNCH(RR, QQ)                                                                                   \
     hipLaunchKernelGGL((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
                        q_used, scale, p.segs_per_wave)
@@ -361,8 +345,6 @@ static hipError_t launch_small(const uint32_t* planes, const bf16_t* act, const 
     return hipGetLastError();
 }
 
-size_t small_bwd_input_workspace(int64_t T, int64_t N, int q) { return (size_t)q * T * N * 2; }
-
 hipError_t launch_fwd_small(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
                             int64_t K, int q, void* y, hipStream_t st) {
     return launch_small<SMALL_FWD>(packed, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, st);
@@ -372,16 +354,6 @@ hipError_t launch_bwd_alpha_small(const uint32_t* packed, const void* x, const v
                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, hipStream_t st) {
     return launch_small<SMALL_DALPHA>(packed, (const bf16_t*)x, nullptr, (const bf16_t*)dy, dalpha, T, N, K / 32, q,
                                       q_train, grad_scale, st);
-}
-
-hipError_t launch_bwd_input_small(const uint32_t* packed_t, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                  int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
-    const int64_t total = T * N;
-    hipLaunchKernelGGL(scale_dy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t*)dy,
-                       alpha, (bf16_t*)workspace, T, N, q);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return launch_small<SMALL_DX>(packed_t, (const bf16_t*)workspace, nullptr, nullptr, dx, T, K, N / 32, q, q, 1.f, st);
 }
 
 }  // namespace bcq
