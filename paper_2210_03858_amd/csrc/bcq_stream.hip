@@ -149,7 +149,9 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
 // ---------------------------------------------------------------------------------------------------------
 // planes: [q][rows][cw] words (canonical for FWD / DALPHA, twin for DX); xq / sq: output of quant_act_kernel
 // (DX: one set per plane).  rows x 32 cw is the plane matrix seen by this kernel.
-template <int MODE, int R, int QP, bool TWO>
+// QUAD: the plane rows are read 16 bytes per lane (needs cw % 4 == 0); a segment that reaches beyond the row is
+// shifted back inside it - the words it then re-reads meet zero activations.
+template <int MODE, int R, int QP, bool TWO, bool QUAD>
 __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict__ planes,
                                                       const unsigned char* __restrict__ xq,
                                                       const unsigned char* __restrict__ sq,
@@ -173,14 +175,19 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 #pragma unroll
         for (int i = 0; i < NACC; ++i) acc[r][i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint32_t* prow[R];
+    // Addresses are a uniform 64-bit base (scalar registers) plus a 32-bit lane offset: rows * cw <= 2^29 words.
+    const uint32_t cw32 = (uint32_t)cw;
+    uint32_t roff[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         int64_t rr = row0 + 16 * r + rl;
         rr = rr < rows ? rr : rows - 1;  // rows beyond the matrix give outputs that are never stored
-        prow[r] = planes + rr * cw;
+        roff[r] = (uint32_t)(rr * cw);
     }
     const int64_t plane_stride = rows * cw;
+    const uint32_t* pl[PPP];
+#pragma unroll
+    for (int i = 0; i < PPP; ++i) pl[i] = planes + (int64_t)(i < q_used ? i : q_used - 1) * plane_stride;
 
     // result column of this lane -> token: with one half, columns t and t + 8 both belong to token t
     const int tcol = TWO ? rl : (rl & 7);
@@ -204,62 +211,86 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
         }
 
     const int seg_begin = wave * segs_per_wave;
-    const unsigned char* xq_t = xq + (size_t)tile * segs * 4 * H * QBLK + (size_t)lane * 32;
-    const unsigned char* sq_t = sq + (size_t)tile * segs * H * QSCL + (size_t)lane * 4;
+    constexpr int NSET = (MODE == STREAM_DX) ? PPP : 1;  // DX: every plane has its own scaled activations
+    const unsigned char* xqp[NSET];
+    const unsigned char* sqp[NSET];
+#pragma unroll
+    for (int ps = 0; ps < NSET; ++ps) {
+        const int pc = ps < q_used ? ps : q_used - 1;
+        xqp[ps] = xq + (size_t)pc * xq_plane + (size_t)tile * segs * 4 * H * QBLK;
+        sqp[ps] = sq + (size_t)pc * sq_plane + (size_t)tile * segs * H * QSCL;
+    }
+    const uint32_t lane32 = (uint32_t)lane * 32u, lane4 = (uint32_t)lane * 4u;
 
-    for (int s = 0; s < segs_per_wave; ++s) {
-        const int64_t seg = seg_begin + s;
-        if (seg >= segs) break;  // whole wave leaves together
-        const int64_t w0 = seg * 16 + 4 * g;
-        const bool quad = (w0 + 3 < cw) && ((cw & 3) == 0);
-        uint32_t bits[R][PPP][4];
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int i = 0; i < PPP; ++i) {
-                const int ic = i < q_used ? i : q_used - 1;
-                const uint32_t* pr = prow[r] + (int64_t)ic * plane_stride;
-                if (quad) {
-                    const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(pr + w0);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) bits[r][i][j] = v4[j];
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int64_t wj = (w0 + j) < cw ? w0 + j : cw - 1;  // columns beyond C meet zero activations
-                        bits[r][i][j] = pr[wj];
-                    }
-                }
-            }
-        constexpr int NSET = (MODE == STREAM_DX) ? PPP : 1;  // DX: every plane has its own scaled activations
-        int sc[NSET][H];
-#pragma unroll
-        for (int ps = 0; ps < NSET; ++ps) {
-            const int pc = ps < q_used ? ps : q_used - 1;
-#pragma unroll
-            for (int h = 0; h < H; ++h)
-                sc[ps][h] = *reinterpret_cast<const int*>(sq_t + (size_t)pc * sq_plane + ((size_t)seg * H + h) * QSCL);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            q_i32x8 bop[NSET][H];
-#pragma unroll
-            for (int ps = 0; ps < NSET; ++ps) {
-                const int pc = ps < q_used ? ps : q_used - 1;
-#pragma unroll
-                for (int h = 0; h < H; ++h) {
-                    const q_u32x4* bp = reinterpret_cast<const q_u32x4*>(xq_t + (size_t)pc * xq_plane +
-                                                                         (((size_t)seg * 4 + j) * H + h) * QBLK);
-                    const q_u32x4 lo = bp[0], hi = bp[1];
-                    bop[ps][h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
-                                         (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-                }
-            }
+    // Software pipeline: the plane words of the NEXT segment and the activation operand of the NEXT instruction
+    // group are requested before the matrix instructions of the current one are issued.
+    uint32_t bits[2][R][PPP][4];
+    q_i32x8 bop[2][NSET][H];
+    int sc[2][NSET][H];
+    auto load_bits = [&](int seg, int buf) {
+        uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
+        if (QUAD) {
+            w0 = w0 < cw32 - 4u ? w0 : cw32 - 4u;
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int i = 0; i < PPP; ++i) {
-                    const uint32_t wd = bits[r][i][j];
+                    const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(pl[i] + (roff[r] + w0));
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) bits[buf][r][i][jj] = v4[jj];
+                }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < PPP; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        uint32_t wj = w0 + (uint32_t)jj;
+                        wj = wj < cw32 ? wj : cw32 - 1u;  // columns beyond C meet zero activations
+                        bits[buf][r][i][jj] = pl[i][roff[r] + wj];
+                    }
+        }
+#pragma unroll
+        for (int ps = 0; ps < NSET; ++ps)
+#pragma unroll
+            for (int h = 0; h < H; ++h)
+                sc[buf][ps][h] = *reinterpret_cast<const int*>(sqp[ps] + (uint32_t)((seg * H + h) * QSCL) + lane4);
+    };
+    auto load_bop = [&](int seg, int jj, int buf) {
+#pragma unroll
+        for (int ps = 0; ps < NSET; ++ps)
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const unsigned char* bp = xqp[ps] + (uint32_t)(((seg * 4 + jj) * H + h) * QBLK);
+                const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp + lane32);
+                const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + lane32 + 16u);
+                bop[buf][ps][h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
+                                          (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            }
+    };
+    int seg_end = seg_begin + segs_per_wave;
+    seg_end = seg_end < (int)segs ? seg_end : (int)segs;
+    if (seg_begin < seg_end) {  // uniform per wave
+        load_bits(seg_begin, 0);
+        load_bop(seg_begin, 0, 0);
+    }
+    for (int seg = seg_begin; seg < seg_end; ++seg) {
+        const int nseg = (seg + 1 < seg_end) ? seg + 1 : seg;  // the last segment re-requests itself (unused)
+        load_bits(nseg, 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j < 3)
+                load_bop(seg, j + 1, (j + 1) & 1);
+            else
+                load_bop(nseg, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < PPP; ++i) {
+                    const uint32_t wd = bits[0][r][i][j];
                     q_i32x8 aop;
 #pragma unroll
                     for (int sft = 0; sft < 4; ++sft) aop[sft] = (int)(((wd << sft) & 0x88888888u) ^ 0xAAAAAAAAu);
@@ -274,17 +305,31 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 #pragma unroll
                     for (int h = 0; h < H; ++h) {
                         // the instruction picks byte j of the scale register (its op_sel), so j must be a constant
+                        const q_i32x8 bo = bop[j & 1][ps][h];
+                        const int sv = sc[0][ps][h];
                         if (j == 0)
-                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 0, sc[ps][h]);
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo, acc[r][ai], 4, 0, 0, scale_a, 0, sv);
                         else if (j == 1)
-                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 1, sc[ps][h]);
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo, acc[r][ai], 4, 0, 0, scale_a, 1, sv);
                         else if (j == 2)
-                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 2, sc[ps][h]);
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo, acc[r][ai], 4, 0, 0, scale_a, 2, sv);
                         else
-                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bop[ps][h], acc[r][ai], 4, 0, 0, scale_a, 3, sc[ps][h]);
+                            acc[r][ai] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo, acc[r][ai], 4, 0, 0, scale_a, 3, sv);
                     }
                 }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // hand the prefetched segment over (register moves; the next iteration's requests go to buffer 1 again)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < PPP; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) bits[0][r][i][jj] = bits[1][r][i][jj];
+#pragma unroll
+        for (int ps = 0; ps < NSET; ++ps)
+#pragma unroll
+            for (int h = 0; h < H; ++h) sc[0][ps][h] = sc[1][ps][h];
     }
 
     // one half: add the second term's columns (t + 8) onto the first term's (t); lanes l and l ^ 8 swap
@@ -382,7 +427,9 @@ static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw) {
     p.segs = (cw + 15) / 16;
     p.halves = T <= 8 ? 1 : 2;
     p.tiles = (int)((T + 15) / 16);
-    p.R = rows >= 16384 ? 2 : 1;
+    // One 16-row tile per wave: measured faster than two at every size (more waves keep more plane bytes in flight,
+    // which is what bounds the stream; the activation operand is L2-resident either way).
+    p.R = 1;
     const int64_t blocks = (rows + 16 * p.R - 1) / (16 * p.R);
     // waves per workgroup: aim at about two waves per SIMD (2048 on the chip); among the candidates from there up to
     // 8 take the first that keeps every wave at least 80 % loaded, else the best balanced
@@ -405,7 +452,11 @@ static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw) {
     }
     p.W = best_w;
     p.segs_per_wave = (int)((p.segs + best_w - 1) / best_w);
-    p.grid_x = (unsigned)blocks;
+#ifdef BCQ_PROBE_PLAN
+    if (getenv("BCQ_R")) p.R = atoi(getenv("BCQ_R"));
+    if (getenv("BCQ_W")) { p.W = atoi(getenv("BCQ_W")); if (p.W > p.segs) p.W = (int)p.segs; p.segs_per_wave = (int)((p.segs + p.W - 1) / p.W); }
+#endif
+    p.grid_x = (unsigned)((rows + 16 * p.R - 1) / (16 * p.R));
     p.xq_bytes = (size_t)p.tiles * p.segs * 4 * p.halves * QBLK;
     p.sq_bytes = (size_t)p.tiles * p.segs * p.halves * QSCL;
     return p;
@@ -438,9 +489,14 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
     const int qp = q_used <= 4 ? q_used : 8;
-#define BCQ_STREAM_LAUNCH(RR, QQ, TT)                                                                                  \
-    hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, rows,   \
-                       cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127)
+    const bool quad = (cw % 4 == 0);
+#define BCQ_STREAM_LAUNCH(RR, QQ, TT)                                                                                    \
+    if (quad)                                                                                                            \
+        hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT, true>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, \
+                           T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127);             \
+    else                                                                                                                 \
+        hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT, false>), grid, block, lds, st, planes, xq, sq, alpha, dy,     \
+                           out, T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127)
 #define BCQ_STREAM_Q(RR, TT)                                      \
     switch (qp) {                                                 \
         case 1: BCQ_STREAM_LAUNCH(RR, 1, TT); break;              \
@@ -449,18 +505,11 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
         case 4: BCQ_STREAM_LAUNCH(RR, 4, TT); break;              \
         default: BCQ_STREAM_LAUNCH(RR, 8, TT); break;             \
     }
+    if (p.R != 1) return hipErrorInvalidConfiguration;  // only the one-tile-per-wave form is instantiated
     if (p.halves == 2) {
-        if (p.R == 2) {
-            BCQ_STREAM_Q(2, true)
-        } else {
-            BCQ_STREAM_Q(1, true)
-        }
+        BCQ_STREAM_Q(1, true)
     } else {
-        if (p.R == 2) {
-            BCQ_STREAM_Q(2, false)
-        } else {
-            BCQ_STREAM_Q(1, false)
-        }
+        BCQ_STREAM_Q(1, false)
     }
 #undef BCQ_STREAM_Q
 #undef BCQ_STREAM_LAUNCH
