@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--g", type=int, default=0,
                     help="group size of the scales along K (Table 4); 0 = row-wise (g = h_in), the headline workload; "
                          "a layer with K < g uses g = K")
+    ap.add_argument("--layer", type=str, default="",
+                    help="time ONE layer of shape NxK (e.g. 16384x16384) instead of the workload's four layer shapes; "
+                         "seeds, dtype and q still come from --config")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the two context measurements (device-to-device copy, plain bf16 GEMMs of the same "
                          "shapes through the vendor BLAS that PyTorch links)")
@@ -82,10 +85,18 @@ def main():
     tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
     code = bcq.binding.BCQ_BF16 if dtype == "bf16" else bcq.binding.BCQ_F32
     kinds = cfg["kinds"]
+    custom = None
+    if args.layer:
+        custom = tuple(int(v) for v in args.layer.lower().split("x"))
+        assert len(custom) == 2 and custom[1] % 32 == 0, "--layer wants NxK with K % 32 == 0"
+        kinds = ("out",)  # seeds of the (h, h) layer
+
+    def shape_of(kind):
+        return custom if custom else synth.layer_shape(h, kind)
 
     small = T < 32            # streaming regime: bound by HBM, measured over a stack of distinct layers
     use_graph = args.graph or small
-    block_packed = sum(synth.layer_shape(h, k)[0] * synth.layer_shape(h, k)[1] for k in kinds) * q // 8
+    block_packed = sum(shape_of(k)[0] * shape_of(k)[1] for k in kinds) * q // 8
     replicas = args.replicas or (max(1, -(-(512 << 20) // block_packed)) if small else 1)
 
     # ---------------- one-time setup: synthetic weights -> greedy BCQ on the GPU, twin, activations
@@ -93,7 +104,7 @@ def main():
     setup_ms = {"quantize": 0.0, "pack_transposed": 0.0}
     weights_total = 0
     for rep, kind in [(r, k) for r in range(replicas) for k in kinds]:
-        N, K = synth.layer_shape(h, kind)
+        N, K = shape_of(kind)
         W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"], extra=rep)).cuda()
         g = min(args.g, K) if args.g else K
         e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
@@ -258,10 +269,10 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import bcq_oracle as oracle
         budget_s, spent, flops_done, done = 12.0, 0.0, 0.0, []
-        for kind in sorted(kinds, key=lambda k: synth.layer_shape(h, k)[0] * synth.layer_shape(h, k)[1]):
+        for kind in sorted(kinds, key=lambda k: shape_of(k)[0] * shape_of(k)[1]):
             if spent > budget_s:
                 break
-            N, K = synth.layer_shape(h, kind)
+            N, K = shape_of(kind)
             W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
             gl = min(args.g, K) if args.g else K
             a_ref, planes_ref = oracle.quantize(W, q, g=gl)
@@ -293,7 +304,7 @@ def main():
         "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s scales, %s activations, T=%d tokens; "
-                               "fwd+dx+dalpha" % (args.config, h, "/".join(kinds), q,
+                               "fwd+dx+dalpha" % (args.config, h, ("one %dx%d layer" % custom) if custom else "/".join(kinds), q,
                                                   ("g=%d group-wise" % args.g) if args.g else "row-wise", dtype, T),
                    "h": h, "q": q, "tokens": T, "g": args.g or "h_in", "weights_per_block": weights_total // replicas,
                    "layer_stack_replicas": replicas, "hip_graph": graph is not None},

@@ -1,74 +1,128 @@
 // Greedy BCQ quantizer (AlphaTuning Appendix C: Eq. ap1 for the first plane, Eq. ap2-ap3 for the rest).
-// One 256-thread workgroup per row of W.  The fp64 residual of the whole row stays in registers across the
-// q planes, so W is read from HBM exactly once (4 N K bytes) and only alpha and the packed signs are
-// written.  HBM bound; the fp64 abs-sum, compare and subtract are a few ALU operations per weight.
+// The fp64 residual of a whole row stays in registers across the q planes, so W is read from HBM exactly once
+// (4 N K bytes) and only alpha and the packed signs are written.  HBM bound; the fp64 abs-sum, compare and
+// subtract are a few ALU operations per weight.  Rows of up to 4096 columns take one WAVE each (four rows per
+// workgroup, no LDS, no barrier: the per-plane sum is a wave reduction); longer rows take one 256-thread
+// workgroup each with the four waves' sums combined through LDS.
 //
 // Arithmetic (what makes the sign planes reproducible bit for bit): residual and abs-sum in fp64, mean
 // rounded once to fp32, that fp32 value subtracted.  Only the ORDER of the fp64 sum is free.
 #include "bcq_internal.h"
 
+#include <type_traits>
+
 namespace bcq {
 
-// Wave w of the block owns columns [w*C*64, (w+1)*C*64); lane l holds column w*C*64 + c*64 + l in r[c].
-template <int CMAX>
+// compile-time loop: f(std::integral_constant<int, C>) for C = BEGIN .. END - 1
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+// dst[lane L] = v (v wave-uniform); the lane index must be an instruction constant.  The scalar operand is usually
+// the result of a vector compare issued just before; inside inline assembly the compiler cannot see that
+// dependency, so the wait states the hardware wants between a vector write of a scalar register and its use here
+// are spelled out.
+template <int L>
+__device__ __forceinline__ void write_lane(uint32_t& dst, uint32_t v) {
+    asm volatile("s_nop 4\n\tv_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(v), "n"(L));
+}
+
+// Chunk cc of a row = columns 64 cc .. 64 cc + 63.  WAVE_ROW = true: wave w owns the whole row 4 blockIdx.x + w,
+// register r[c] of lane l holds column 64 c + l.  WAVE_ROW = false: the four waves of the block share row
+// blockIdx.x, wave w takes chunks 4 c + w.  Either way every chunk of a wave is entirely inside the row except
+// at most one (K % 64 == 32), so all guards are wave-uniform but one lane mask.
+//
+// Signs come from the sign bit of the residual: the weights are normalised with + 0.0 on load (-0.0 -> +0.0) and
+// x - x = +0.0 afterwards, so "sign bit clear" is exactly r >= 0 (rows with NaN have unspecified outputs).
+// The wave-uniform ballot of chunk c goes into lane c with v_writelane, so that the packed words leave as one
+// coalesced store per plane; the subtraction r -= alpha * b is r - copysign(alpha, r) on the high word.
+// EXACT: every wave has exactly CMAX whole chunks (K == 64 NW CMAX), so no guard is needed at all.
+template <int CMAX, bool WAVE_ROW, bool EXACT>
 __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W, int64_t N, int K, int q,
                                                        float* __restrict__ alpha, uint32_t* __restrict__ packed,
                                                        int8_t* __restrict__ planes, int* __restrict__ status_word) {
     __shared__ double wave_sum[4];
-    const int64_t n = blockIdx.x;
+    constexpr int NW = WAVE_ROW ? 1 : 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int C = (K + 255) / 256;  // <= CMAX
-    const int kbase = wave * C * 64;
+    const int64_t n = WAVE_ROW ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    if (WAVE_ROW && n >= N) return;  // whole wave leaves; this form has no barrier
+    const int wv = WAVE_ROW ? 0 : wave;
     const float* wrow = W + n * (int64_t)K;
     const int Kw = K / 32;
+    // chunks of this wave that reach into the row (uniform), and whether the last of them is only half inside
+    const int chunks_row = (K + 63) / 64;
+    const int nch = EXACT ? CMAX : (chunks_row > wv ? (chunks_row - wv + NW - 1) / NW : 0);  // <= CMAX
+    const int last = nch - 1;
+    const bool last_half = !EXACT && (nch > 0) && (((last * NW + wv) * 64 + 64) > K);
+    const bool lane_in_last = !last_half || lane < 32;
 
     double r[CMAX];
 #pragma unroll
     for (int c = 0; c < CMAX; ++c) {
-        int k = kbase + c * 64 + lane;
-        r[c] = (c < C && k < K) ? (double)wrow[k] : 0.0;
+        r[c] = 0.0;
+        if (EXACT || c < nch) {
+            const int k = (c * NW + wv) * 64 + lane;
+            if (EXACT || c < last || lane_in_last) r[c] = (double)wrow[k] + 0.0;
+        }
     }
 
     for (int i = 0; i < q; ++i) {
         double s = 0.0;
-        uint64_t mine = 0;  // lane c keeps the 64 sign bits of chunk c
-#pragma unroll
-        for (int c = 0; c < CMAX; ++c) {
-            if (c < C) {
+        uint32_t mine_lo = 0u, mine_hi = 0u;
+        static_for<0, CMAX>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            if (EXACT || c < nch) {
                 s += fabs(r[c]);
-                uint64_t m = __ballot(r[c] >= 0.0);
-                if (lane == c) mine = m;
+                const uint64_t m = __ballot((int)__double2hiint(r[c]) >= 0);  // sign bit clear <=> +1
+                write_lane<c>(mine_lo, (uint32_t)m);                          // the ballot is wave-uniform
+                write_lane<c>(mine_hi, (uint32_t)(m >> 32));
             }
-        }
-        // workgroup sum of |r| in fp64
+        });
+        // sum of |r| over the row in fp64
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-        __syncthreads();  // wave_sum of the previous plane has been read by everyone
-        if (lane == 0) wave_sum[wave] = s;
-        __syncthreads();
-        const double S = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+        double S = s;
+        if (!WAVE_ROW) {
+            __syncthreads();  // wave_sum of the previous plane has been read by everyone
+            if (lane == 0) wave_sum[wave] = s;
+            __syncthreads();
+            S = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+        }
         const float a = (float)(S / (double)K);
-        if (threadIdx.x == 0) {
+        if (WAVE_ROW ? (lane == 0) : (threadIdx.x == 0)) {
             alpha[(int64_t)i * N + n] = a;
             if (i == 0 && status_word && !(fabs(S) <= 1.79769313486231570e308)) atomicAdd(status_word, 1);
         }
-        // packed words: lane c writes the two words of chunk c (8 bytes, consecutive lanes are contiguous)
-        if (lane < C) {
-            int k0 = kbase + lane * 64;
+        // packed words: lane c writes the two words of its chunk (8 bytes; consecutive lanes are 8 NW bytes apart)
+        if (lane < nch) {
+            const int k0 = (lane * NW + wv) * 64;
             uint32_t* dst = packed + ((int64_t)i * N + n) * Kw + k0 / 32;
-            if (k0 < K) dst[0] = (uint32_t)mine;
-            if (k0 + 32 < K) dst[1] = (uint32_t)(mine >> 32);
+            dst[0] = mine_lo;
+            if (k0 + 32 < K) dst[1] = mine_hi;
         }
+        if (planes) {
+#pragma unroll
+            for (int c = 0; c < CMAX; ++c) {
+                if (EXACT || (c < nch && (c < last || lane_in_last))) {
+                    const int k = (c * NW + wv) * 64 + lane;
+                    planes[((int64_t)i * N + n) * K + k] = ((int)__double2hiint(r[c]) >= 0) ? (int8_t)1 : (int8_t)-1;
+                }
+            }
+        }
+        // r -= alpha * b, b = sign of r: subtract alpha carrying r's sign bit.  Lanes of the half chunk that lie beyond
+        // the row subtract 0, so they stay +0.0 and never add to the abs-sum.
         const double ad = (double)a;
+        const double ad_last = lane_in_last ? ad : 0.0;
 #pragma unroll
         for (int c = 0; c < CMAX; ++c) {
-            if (c < C) {
-                const bool pos = r[c] >= 0.0;
-                const int k = kbase + c * 64 + lane;
-                if (k < K) {  // padding lanes keep r = 0 so that they never add to the abs-sum
-                    if (planes) planes[((int64_t)i * N + n) * K + k] = pos ? (int8_t)1 : (int8_t)-1;
-                    r[c] = pos ? r[c] - ad : r[c] + ad;  // r - alpha * b with b = +-1
-                }
+            if (EXACT || c < nch) {
+                const double sub = (!EXACT && c == last) ? ad_last : ad;
+                const int hi = __double2hiint(sub) | (__double2hiint(r[c]) & (int)0x80000000);
+                r[c] -= __hiloint2double(hi, __double2loint(sub));
             }
         }
     }
@@ -76,11 +130,16 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
 
 __global__ void zero_word_kernel(int* p) { *p = 0; }
 
-template <int CMAX>
+template <int CMAX, bool WAVE_ROW>
 static hipError_t launch_q(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                            int8_t* planes, int* status_word, hipStream_t st) {
-    hipLaunchKernelGGL(quantize_kernel<CMAX>, dim3((unsigned)N), dim3(256), 0, st, W, N, (int)K, q, alpha, packed,
-                       planes, status_word);
+    const unsigned blocks = (unsigned)(WAVE_ROW ? (N + 3) / 4 : N);
+    if (K == (int64_t)64 * (WAVE_ROW ? 1 : 4) * CMAX)
+        hipLaunchKernelGGL((quantize_kernel<CMAX, WAVE_ROW, true>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
+                           alpha, packed, planes, status_word);
+    else
+        hipLaunchKernelGGL((quantize_kernel<CMAX, WAVE_ROW, false>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
+                           alpha, packed, planes, status_word);
     return hipGetLastError();
 }
 
@@ -91,13 +150,22 @@ hipError_t launch_quantize(const float* W, int64_t N, int64_t K, int q, float* a
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+#define BCQ_Q_PICK(MODE)                                                                        \
+    if (C <= 2) return launch_q<2, MODE>(W, N, K, q, alpha, packed, planes, status_word, st);   \
+    if (C <= 4) return launch_q<4, MODE>(W, N, K, q, alpha, packed, planes, status_word, st);   \
+    if (C <= 8) return launch_q<8, MODE>(W, N, K, q, alpha, packed, planes, status_word, st);   \
+    if (C <= 16) return launch_q<16, MODE>(W, N, K, q, alpha, packed, planes, status_word, st); \
+    if (C <= 20) return launch_q<20, MODE>(W, N, K, q, alpha, packed, planes, status_word, st); \
+    if (C <= 32) return launch_q<32, MODE>(W, N, K, q, alpha, packed, planes, status_word, st); \
+    if (C <= 40) return launch_q<40, MODE>(W, N, K, q, alpha, packed, planes, status_word, st); \
+    return launch_q<64, MODE>(W, N, K, q, alpha, packed, planes, status_word, st);
+    if (K <= 4096) {  // one wave per row
+        const int C = (int)((K + 63) / 64);
+        BCQ_Q_PICK(true)
+    }
     const int C = (int)((K + 255) / 256);
-    if (C <= 4) return launch_q<4>(W, N, K, q, alpha, packed, planes, status_word, st);
-    if (C <= 8) return launch_q<8>(W, N, K, q, alpha, packed, planes, status_word, st);
-    if (C <= 16) return launch_q<16>(W, N, K, q, alpha, packed, planes, status_word, st);
-    if (C <= 24) return launch_q<24>(W, N, K, q, alpha, packed, planes, status_word, st);
-    if (C <= 40) return launch_q<40>(W, N, K, q, alpha, packed, planes, status_word, st);
-    return launch_q<64>(W, N, K, q, alpha, packed, planes, status_word, st);
+    BCQ_Q_PICK(false)
+#undef BCQ_Q_PICK
 }
 
 }  // namespace bcq
