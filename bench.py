@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # HBM-side bytes per launch of the dominant kernel of the default workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy); see
 # profiles/bench_config2_hbm_traffic.md for the commands and the table.  Not measured live: null for other workloads.
-PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.6e7, (2, 4096, 4, "bwd_input"): 7.6e7}
+PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.76e7, (2, 4096, 4, "bwd_input"): 7.76e7}
 
 
 def parse():
