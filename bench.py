@@ -65,7 +65,8 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are part of "
-              "the BCQ linear hot path; see DESIGN.md for how it would shard)" % args.gpus, file=sys.stderr)
+              "the BCQ linear hot path: rows of W shard without any exchange except one all-reduce of dx)" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
