@@ -63,8 +63,20 @@ constexpr int64_t kMfmaMinTokens = 32;
 // the contraction over all of K).  Group-wise scales take the tiled kernels at every token count.
 bool small_fwd_ok(int64_t T, bool rowwise, int dtype) { return dtype == BCQ_BF16 && rowwise && T < kMfmaMinTokens; }
 bool small_bwd_alpha_ok(int64_t T, bool rowwise, int dtype) { return dtype == BCQ_BF16 && rowwise && T <= 16; }
-bool small_bwd_input_ok(int64_t T, int64_t N, bool rowwise, int dtype) {
-    return dtype == BCQ_BF16 && rowwise && T < kMfmaMinTokens && N % 32 == 0;
+
+// Streaming kernels (need a workspace): row-wise scales, or group-wise scales whose groups are whole 512-column
+// segments (forward, scale gradient); the input gradient takes any group size (one activation set per plane and
+// group, at most kStreamMaxSets of them).
+constexpr int64_t kStreamMaxSets = 256;
+bool stream_group_ok(int64_t K, int64_t g) { return g == K || g % 512 == 0; }
+bool stream_fwd_ok(int64_t T, int64_t K, int64_t g, int dtype) {
+    return dtype == BCQ_BF16 && T < kMfmaMinTokens && stream_group_ok(K, g);
+}
+bool stream_bwd_alpha_ok(int64_t T, int64_t K, int64_t g, int dtype) {
+    return dtype == BCQ_BF16 && T <= 16 && stream_group_ok(K, g);
+}
+bool stream_bwd_input_ok(int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype) {
+    return dtype == BCQ_BF16 && T < kMfmaMinTokens && N % 32 == 0 && q * (K / g) <= kStreamMaxSets;
 }
 
 bool mfma_fwd_ok(int64_t T, bool rowwise, int dtype) {
@@ -82,13 +94,17 @@ size_t workspace_need(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q,
     switch (op) {
         case BCQ_OP_QUANTIZE: return 16;  // status word
         case BCQ_OP_FWD:
-            if (small_fwd_ok(T, rowwise, dtype)) return bcq::stream_fwd_workspace(T, K);
+            if (stream_fwd_ok(T, K, g, dtype)) return bcq::stream_fwd_workspace(T, K);
             return mfma_fwd_ok(T, rowwise, dtype) ? bcq::mfma_fwd_workspace(N, K) : 0;
-        case BCQ_OP_BWD_INPUT:
-            if (small_bwd_input_ok(T, N, rowwise, dtype)) return bcq::stream_bwd_input_workspace(T, N, q);
-            return mfma_bwd_input_ok(T, N, rowwise, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
+        case BCQ_OP_BWD_INPUT: {
+            // which path runs depends on the twin being passed, so the size covers both candidates
+            const size_t a = stream_bwd_input_ok(T, N, K, g, q, dtype)
+                                 ? bcq::stream_bwd_input_workspace(T, N, (int)(q * (K / g))) : 0;
+            const size_t b = mfma_bwd_input_ok(T, N, rowwise, dtype) ? bcq::mfma_bwd_input_workspace(N, K) : 0;
+            return a > b ? a : b;
+        }
         case BCQ_OP_BWD_ALPHA:
-            if (small_bwd_alpha_ok(T, rowwise, dtype)) return bcq::stream_bwd_alpha_workspace(T, K);
+            if (stream_bwd_alpha_ok(T, K, g, dtype)) return bcq::stream_bwd_alpha_workspace(T, K);
             return mfma_bwd_alpha_ok(T, N, K, rowwise, dtype) ? bcq::mfma_bwd_alpha_workspace(T, N, K, g, q) : 0;
         default: return 0;
     }
@@ -226,10 +242,9 @@ bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, co
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
-    if (small_fwd_ok(T, rowwise, dtype)) {
-        if (workspace) return done(bcq::launch_fwd_stream(packed, alpha, x, T, N, K, q, y, workspace, st));
-        return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, st));
-    }
+    if (workspace && stream_fwd_ok(T, K, g, dtype))
+        return done(bcq::launch_fwd_stream(packed, alpha, x, T, N, K, g, q, y, workspace, st));
+    if (small_fwd_ok(T, rowwise, dtype)) return done(bcq::launch_fwd_small(packed, alpha, x, T, N, K, q, y, st));
     if (workspace && mfma_fwd_ok(T, rowwise, dtype))
         return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, g, q, y, workspace, st));
     return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, g, q, y, st));
@@ -259,8 +274,8 @@ bcq_status bcq_linear_bwd_input_grouped(const uint32_t* packed, const uint32_t* 
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
-    if (workspace && packed_t && small_bwd_input_ok(T, N, rowwise, dtype))
-        return done(bcq::launch_bwd_input_stream(packed_t, alpha, dy, T, N, K, q, dx, workspace, st));
+    if (workspace && packed_t && stream_bwd_input_ok(T, N, K, g, q, dtype))
+        return done(bcq::launch_bwd_input_stream(packed_t, alpha, dy, T, N, K, g, q, dx, workspace, st));
     if (workspace && mfma_bwd_input_ok(T, N, rowwise, dtype))
         return done(bcq::launch_bwd_input_mfma(packed, packed_t, alpha, dy, T, N, K, g, q, dx, workspace, st));
     return done(bcq::launch_bwd_input_generic(packed, alpha, dy, dtype, T, N, K, g, q, dx, st));
@@ -358,12 +373,12 @@ bcq_status bwd_alpha_impl(const uint32_t* packed, const void* x, const void* dy,
     if (s != BCQ_OK) return s;
     const bool rowwise = (g == K);
     hipStream_t st = (hipStream_t)stream;
-    if (workspace && small_bwd_alpha_ok(T, rowwise, dtype)) {
-        hipError_t e = bcq::launch_bwd_alpha_stream(packed, x, dy, T, N, K, q, q_train, grad_scale, dalpha, workspace, st);
+    if (workspace && stream_bwd_alpha_ok(T, K, g, dtype)) {
+        hipError_t e = bcq::launch_bwd_alpha_stream(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace, st);
         if (e == hipSuccess && with_opt) e = bcq::launch_adamw(dalpha, (int64_t)q_train * N * (K / g), oargs, st);
         return done(e);
     }
-    if (workspace && !small_bwd_alpha_ok(T, rowwise, dtype) && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
+    if (workspace && !stream_bwd_alpha_ok(T, K, g, dtype) && mfma_bwd_alpha_ok(T, N, K, rowwise, dtype))
         return done(bcq::launch_bwd_alpha_mfma(packed, x, dy, T, N, K, g, q, q_train, grad_scale, dalpha, workspace,
                                                with_opt ? &oargs : nullptr, st));
     hipError_t e;

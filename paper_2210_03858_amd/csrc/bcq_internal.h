@@ -95,17 +95,17 @@ hipError_t launch_fwd_small(const uint32_t* packed, const float* alpha, const vo
 hipError_t launch_bwd_alpha_small(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, hipStream_t st);
 
-// ---- small-token kernels on the block-scaled FP4 x FP8 matrix instruction (bf16, row-wise scales; need a
-// workspace for the activations re-coded as two FP8 terms) ----
+// ---- small-token kernels on the block-scaled FP4 x FP8 matrix instruction (bf16; row-wise scales, or group-wise
+// with g % 512 == 0 for forward / scale gradient; need a workspace for the activations re-coded as two FP8 terms) ----
 size_t stream_fwd_workspace(int64_t T, int64_t K);
 size_t stream_bwd_alpha_workspace(int64_t T, int64_t K);
-size_t stream_bwd_input_workspace(int64_t T, int64_t N, int q);
+size_t stream_bwd_input_workspace(int64_t T, int64_t N, int sets /* q * (K / g) */);
 hipError_t launch_fwd_stream(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
-                             int64_t K, int q, void* y, void* workspace, hipStream_t st);
+                             int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st);
 hipError_t launch_bwd_alpha_stream(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
-                                   hipStream_t st);
+                                   int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                                   void* workspace, hipStream_t st);
 hipError_t launch_bwd_input_stream(const uint32_t* packed_t, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                   int64_t K, int q, void* dx, void* workspace, hipStream_t st);
+                                   int64_t K, int64_t g, int q, void* dx, void* workspace, hipStream_t st);
 
 }  // namespace bcq

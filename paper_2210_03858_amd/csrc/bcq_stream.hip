@@ -58,12 +58,13 @@ __device__ __forceinline__ uint32_t q_pack_bf16x2(float lo, float hi) {
 // Pre-kernel: activations -> two block-scaled FP8 terms in operand order.
 // One thread per (token tile, segment, instruction j, token, 32-index block G): it owns packed-word position
 // 16 seg + 4 G + j of the contraction axis (32 columns), finds the block's power-of-two scale, and writes
-// 2 x 16 bytes per term plus the scale bytes.  DX: the activation is dy[t][n] * alpha_i[n] for plane i = blockIdx.y.
+// 2 x 16 bytes per term plus the scale bytes.  DX: the activation is dy[t][n] * alpha_i[n][grp] for set
+// blockIdx.y = i NG + grp (NG scale groups along the columns of W; row-wise scales: NG = 1).
 template <int MODE>
 __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict__ act, const float* __restrict__ alpha,
                                                         int64_t T, int64_t C, int64_t segs, int halves, int tiles,
                                                         unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
-                                                        size_t xq_plane, size_t sq_plane) {
+                                                        size_t xq_plane, size_t sq_plane, int NG) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
     const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
@@ -88,9 +89,10 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
             }
         }
         if (MODE == STREAM_DX) {
-            const float* a = alpha + (int64_t)plane * C + word * 32;
+            const int pl_i = plane / NG, grp = plane % NG;
+            const float* a = alpha + ((int64_t)pl_i * C + word * 32) * NG + grp;  // alpha[i][n][grp], n = 32 word + e
 #pragma unroll
-            for (int e = 0; e < 32; ++e) v[e] *= a[e];
+            for (int e = 0; e < 32; ++e) v[e] *= a[(int64_t)e * NG];
         }
     } else {
 #pragma unroll
@@ -151,14 +153,19 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
 // (DX: one set per plane).  rows x 32 cw is the plane matrix seen by this kernel.
 // QUAD: the plane rows are read 16 bytes per lane (needs cw % 4 == 0); a segment that reaches beyond the row is
 // shifted back inside it - the words it then re-reads meet zero activations.
-template <int MODE, int R, int QP, bool TWO, bool QUAD>
+// GROUPED: group-wise scales alpha[q][N][G].  Forward: the plane sums are folded into y with the group's scales at
+// every group boundary (gsegs segments).  Scale gradient: every group's sums are reduced over the tokens and stored
+// at its end; the host gives every wave whole groups, so no cross-wave sum is needed.  Input gradient: the set of
+// re-coded activations is chosen by the group of the workgroup's rows (dxg rows of the twin per group).
+template <int MODE, int R, int QP, bool TWO, bool QUAD, bool GROUPED>
 __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict__ planes,
                                                       const unsigned char* __restrict__ xq,
                                                       const unsigned char* __restrict__ sq,
                                                       const float* __restrict__ alpha, const bf16_t* __restrict__ dy,
                                                       void* __restrict__ out, int64_t T, int64_t rows, int64_t cw,
                                                       int q_used, float scale, int segs_per_wave, int64_t segs,
-                                                      size_t xq_plane, size_t sq_plane, int scale_a) {
+                                                      size_t xq_plane, size_t sq_plane, int scale_a, int gsegs, int G,
+                                                      int64_t dxg) {
     extern __shared__ __attribute__((aligned(16))) float red[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
     const int rl = lane & 15, g = lane >> 4;
@@ -204,7 +211,8 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
             n = n_live ? n : rows - 1;
             if (MODE == STREAM_FWD) {
 #pragma unroll
-                for (int i = 0; i < QP; ++i) ep[r][i][v] = (i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+                for (int i = 0; i < QP; ++i)
+                    ep[r][i][v] = (!GROUPED && i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
             } else if (MODE == STREAM_DALPHA) {
                 ep[r][0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
             }
@@ -216,7 +224,8 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
     const unsigned char* sqp[NSET];
 #pragma unroll
     for (int ps = 0; ps < NSET; ++ps) {
-        const int pc = ps < q_used ? ps : q_used - 1;
+        int pc = ps < q_used ? ps : q_used - 1;
+        if (GROUPED && MODE == STREAM_DX) pc = pc * G + (int)(row0 / dxg);  // the 16 R rows lie in one group (g % 32 == 0)
         xqp[ps] = xq + (size_t)pc * xq_plane + (size_t)tile * segs * 4 * H * QBLK;
         sqp[ps] = sq + (size_t)pc * sq_plane + (size_t)tile * segs * H * QSCL;
     }
@@ -271,12 +280,29 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
     };
     int seg_end = seg_begin + segs_per_wave;
     seg_end = seg_end < (int)segs ? seg_end : (int)segs;
+    // group-wise scales (forward / scale gradient): y accumulated over the groups, scales of the current group
+    q_f32x4 yv[R];
+    float ga[R][QP][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r) yv[r] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+    auto load_group_alpha = [&](int grp) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                int64_t n = row0 + 16 * r + 4 * g + v;
+                n = n < rows ? n : rows - 1;
+#pragma unroll
+                for (int i = 0; i < QP; ++i) ga[r][i][v] = (i < q_used) ? alpha[((int64_t)i * rows + n) * G + grp] : 0.f;
+            }
+    };
     if (seg_begin < seg_end) {  // uniform per wave
         load_bits(seg_begin, 0);
         load_bop(seg_begin, 0, 0);
     }
     for (int seg = seg_begin; seg < seg_end; ++seg) {
         const int nseg = (seg + 1 < seg_end) ? seg + 1 : seg;  // the last segment re-requests itself (unused)
+        if (GROUPED && MODE == STREAM_FWD && (seg == seg_begin || seg % gsegs == 0)) load_group_alpha(seg / gsegs);
         load_bits(nseg, 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -319,6 +345,43 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
                 }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (GROUPED && MODE != STREAM_DX && ((seg + 1) % gsegs == 0 || seg + 1 == seg_end)) {  // uniform: a group ends
+            const int grp = seg / gsegs;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (MODE == STREAM_FWD) {
+#pragma unroll
+                    for (int i = 0; i < QP; ++i)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) yv[r][v] += ga[r][i][v] * acc[r][i][v];
+                } else {
+                    // both columns of a token (t and t + 8 with one half) carry dy of that token: the 16-lane sum
+                    // adds the two terms and the tokens at once
+                    const int64_t n = row0 + 16 * r + 4 * g;
+#pragma unroll
+                    for (int o = 0; o < QP; ++o)
+                        if (o < q_used) {
+                            q_f32x4 sum;
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                float x = ep[r][0][v] * acc[r][o][v];
+                                x += __shfl_xor(x, 1);
+                                x += __shfl_xor(x, 2);
+                                x += __shfl_xor(x, 4);
+                                x += __shfl_xor(x, 8);
+                                sum[v] = x * scale;
+                            }
+                            if (rl == 0)
+#pragma unroll
+                                for (int v = 0; v < 4; ++v)
+                                    if (n + v < rows)
+                                        reinterpret_cast<float*>(out)[(((int64_t)o * rows + n + v) * G) + grp] = sum[v];
+                        }
+                }
+#pragma unroll
+                for (int i = 0; i < NACC; ++i) acc[r][i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
         // hand the prefetched segment over (register moves; the next iteration's requests go to buffer 1 again)
 #pragma unroll
         for (int r = 0; r < R; ++r)
@@ -332,6 +395,21 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
             for (int h = 0; h < H; ++h) sc[0][ps][h] = sc[1][ps][h];
     }
 
+    if (GROUPED && MODE == STREAM_DALPHA) return;  // every group was stored at its end
+    if (GROUPED && MODE == STREAM_FWD) {            // continue below with y in place of the plane sums
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            acc[r][0] = yv[r];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ep[r][0][v] = 1.f;
+#pragma unroll
+            for (int i = 1; i < QP; ++i) {
+                acc[r][i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) ep[r][i][v] = 0.f;
+            }
+        }
+    }
     // one half: add the second term's columns (t + 8) onto the first term's (t); lanes l and l ^ 8 swap
     if (!TWO) {
 #pragma unroll
@@ -422,7 +500,8 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------------------
-static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw) {
+// gsegs > 0: the contraction axis carries scale groups of gsegs segments each and every wave must own whole groups
+static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw, int gsegs = 0) {
     StreamPlan p;
     p.segs = (cw + 15) / 16;
     p.halves = T <= 8 ? 1 : 2;
@@ -452,6 +531,13 @@ static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw) {
     }
     p.W = best_w;
     p.segs_per_wave = (int)((p.segs + best_w - 1) / best_w);
+    if (gsegs > 0) {  // whole groups per wave
+        const int64_t groups = p.segs / gsegs;
+        if (p.W > groups) p.W = (int)groups;
+        const int64_t gpw = (groups + p.W - 1) / p.W;
+        p.W = (int)((groups + gpw - 1) / gpw);
+        p.segs_per_wave = (int)(gpw * gsegs);
+    }
 #ifdef BCQ_PROBE_PLAN
     if (getenv("BCQ_R")) p.R = atoi(getenv("BCQ_R"));
     if (getenv("BCQ_W")) { p.W = atoi(getenv("BCQ_W")); if (p.W > p.segs) p.W = (int)p.segs; p.segs_per_wave = (int)((p.segs + p.W - 1) / p.W); }
@@ -467,20 +553,24 @@ size_t stream_workspace(int64_t T, int64_t contraction, int sets) {
     return (size_t)sets * (p.xq_bytes + p.sq_bytes);
 }
 
+// g = group size of the scales along the columns of W (K of the layer); g == layer K means row-wise.
 template <int MODE>
 static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
                                 int64_t T, int64_t rows, int64_t cw, int q, int q_used, float scale, void* workspace,
-                                hipStream_t st) {
-    const StreamPlan p = stream_plan(T, rows, cw);
-    if (p.W < 1 || p.W > 8) return hipErrorInvalidConfiguration;  // the kernel is compiled for at most 512 threads
-    const int sets = (MODE == STREAM_DX) ? q : 1;
+                                int64_t g, int64_t layer_k, hipStream_t st) {
+    const bool grouped = (g != layer_k);
+    const int G = (int)(layer_k / g);
+    const int gsegs = (grouped && MODE != STREAM_DX) ? (int)(g / 512) : 0;  // needs g % 512 == 0 (checked by the caller)
+    const StreamPlan p = stream_plan(T, rows, cw, gsegs);
+    if (p.W < 1 || p.W > 8 || p.R != 1) return hipErrorInvalidConfiguration;  // compiled for at most 512 threads, R = 1
+    const int sets = (MODE == STREAM_DX) ? q * G : 1;
     unsigned char* xq = reinterpret_cast<unsigned char*>(workspace);
     unsigned char* sq = xq + (size_t)sets * p.xq_bytes;
     {
         const int64_t threads = (int64_t)p.tiles * p.segs * 256;
         const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)sets);
         hipLaunchKernelGGL((quant_act_kernel<MODE>), grid, dim3(256), 0, st, act, alpha, T, cw * 32, p.segs, p.halves,
-                           p.tiles, xq, sq, p.xq_bytes, p.sq_bytes);
+                           p.tiles, xq, sq, p.xq_bytes, p.sq_bytes, G);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -490,51 +580,63 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
     const int qp = q_used <= 4 ? q_used : 8;
     const bool quad = (cw % 4 == 0);
-#define BCQ_STREAM_LAUNCH(RR, QQ, TT)                                                                                    \
-    if (quad)                                                                                                            \
-        hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT, true>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, \
-                           T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127);             \
-    else                                                                                                                 \
-        hipLaunchKernelGGL((stream_kernel<MODE, RR, QQ, TT, false>), grid, block, lds, st, planes, xq, sq, alpha, dy,     \
-                           out, T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127)
-#define BCQ_STREAM_Q(RR, TT)                                      \
-    switch (qp) {                                                 \
-        case 1: BCQ_STREAM_LAUNCH(RR, 1, TT); break;              \
-        case 2: BCQ_STREAM_LAUNCH(RR, 2, TT); break;              \
-        case 3: BCQ_STREAM_LAUNCH(RR, 3, TT); break;              \
-        case 4: BCQ_STREAM_LAUNCH(RR, 4, TT); break;              \
-        default: BCQ_STREAM_LAUNCH(RR, 8, TT); break;             \
+#define BCQ_STREAM_GO(QQ, TT, QD, GR)                                                                                  \
+    hipLaunchKernelGGL((stream_kernel<MODE, 1, QQ, TT, QD, GR>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, \
+                       rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127,                  \
+                       gsegs > 0 ? gsegs : 1, G, g)
+#define BCQ_STREAM_GR(QQ, TT, QD)            \
+    if (grouped) {                           \
+        BCQ_STREAM_GO(QQ, TT, QD, true);     \
+    } else {                                 \
+        BCQ_STREAM_GO(QQ, TT, QD, false);    \
     }
-    if (p.R != 1) return hipErrorInvalidConfiguration;  // only the one-tile-per-wave form is instantiated
+#define BCQ_STREAM_QD(QQ, TT)            \
+    if (quad) {                          \
+        BCQ_STREAM_GR(QQ, TT, true)      \
+    } else {                             \
+        BCQ_STREAM_GR(QQ, TT, false)     \
+    }
+#define BCQ_STREAM_Q(TT)                              \
+    switch (qp) {                                     \
+        case 1: BCQ_STREAM_QD(1, TT) break;           \
+        case 2: BCQ_STREAM_QD(2, TT) break;           \
+        case 3: BCQ_STREAM_QD(3, TT) break;           \
+        case 4: BCQ_STREAM_QD(4, TT) break;           \
+        default: BCQ_STREAM_QD(8, TT) break;          \
+    }
     if (p.halves == 2) {
-        BCQ_STREAM_Q(1, true)
+        BCQ_STREAM_Q(true)
     } else {
-        BCQ_STREAM_Q(1, false)
+        BCQ_STREAM_Q(false)
     }
 #undef BCQ_STREAM_Q
-#undef BCQ_STREAM_LAUNCH
+#undef BCQ_STREAM_QD
+#undef BCQ_STREAM_GR
+#undef BCQ_STREAM_GO
     return hipGetLastError();
 }
 
 size_t stream_fwd_workspace(int64_t T, int64_t K) { return stream_workspace(T, K, 1); }
 size_t stream_bwd_alpha_workspace(int64_t T, int64_t K) { return stream_workspace(T, K, 1); }
-size_t stream_bwd_input_workspace(int64_t T, int64_t N, int q) { return stream_workspace(T, N, q); }
+size_t stream_bwd_input_workspace(int64_t T, int64_t N, int sets) { return stream_workspace(T, N, sets); }
 
 hipError_t launch_fwd_stream(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
-                             int64_t K, int q, void* y, void* workspace, hipStream_t st) {
-    return launch_stream<STREAM_FWD>(packed, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, workspace, st);
+                             int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st) {
+    return launch_stream<STREAM_FWD>(packed, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, workspace, g, K,
+                                     st);
 }
 
 hipError_t launch_bwd_alpha_stream(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
-                                   int64_t K, int q, int q_train, float grad_scale, float* dalpha, void* workspace,
-                                   hipStream_t st) {
+                                   int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
+                                   void* workspace, hipStream_t st) {
     return launch_stream<STREAM_DALPHA>(packed, (const bf16_t*)x, nullptr, (const bf16_t*)dy, dalpha, T, N, K / 32, q,
-                                        q_train, grad_scale, workspace, st);
+                                        q_train, grad_scale, workspace, g, K, st);
 }
 
 hipError_t launch_bwd_input_stream(const uint32_t* packed_t, const float* alpha, const void* dy, int64_t T, int64_t N,
-                                   int64_t K, int q, void* dx, void* workspace, hipStream_t st) {
-    return launch_stream<STREAM_DX>(packed_t, (const bf16_t*)dy, alpha, nullptr, dx, T, K, N / 32, q, q, 1.f, workspace, st);
+                                   int64_t K, int64_t g, int q, void* dx, void* workspace, hipStream_t st) {
+    return launch_stream<STREAM_DX>(packed_t, (const bf16_t*)dy, alpha, nullptr, dx, T, K, N / 32, q, q, 1.f, workspace,
+                                    g, K, st);
 }
 
 }  // namespace bcq

@@ -114,7 +114,7 @@ def _run_layer(bcq, oracle, config, kind, T, N, K, g, q, dtype, q_train=None, gr
 SHAPES = [
     # T, N, K, g, q
     (1, 64, 64, 32, 1),        # one token, two groups
-    (4, 1280, 1280, 256, 2),   # few tokens: tiled kernels (group-wise scales never take the streaming kernels)
+    (4, 1280, 1280, 256, 2),   # few tokens, groups that are no whole 512-column segments: tiled kernels
     (8, 96, 160, 32, 3),
     (33, 304, 416, 32, 4),     # per-32-column partial sums, ragged tiles in every extent
     (300, 544, 1024, 512, 3),  # groups of two whole 256-column tiles
@@ -124,6 +124,51 @@ SHAPES = [
     (65, 128, 768, 768, 2),    # g = K through the group-wise entry points
     (70, 264, 2048, 1024, 4),  # g = K / 2, the setting of the OPT experiments (Table 7)
 ]
+
+
+STREAM_SHAPES = [
+    # few tokens with groups of whole 512-column segments: the streaming kernels (with workspace and twin); the
+    # input gradient streams at every group size
+    (1, 64, 1024, 512, 1),
+    (4, 1056, 2048, 512, 4),     # one segment per group
+    (8, 320, 3072, 1024, 3),     # three groups: waves own whole groups
+    (9, 96, 4096, 2048, 8),      # two halves (T > 8), every plane
+    (16, 512, 5120, 512, 2),     # ten groups over up to eight waves
+    (31, 64, 1536, 512, 4),      # two token tiles (forward and input gradient only stream here)
+    (5, 160, 1280, 64, 4),       # small groups: only the input gradient streams (20 sets per plane)
+    (8, 2560, 1024, 512, 4),
+]
+
+
+@pytest.mark.parametrize("T,N,K,g,q", STREAM_SHAPES)
+def test_grouped_small_token_streaming_parity(bcq, oracle, T, N, K, g, q):
+    for workspace, twin in ((True, True), (True, False), (False, False)):
+        _run_layer(bcq, oracle, 3, "out", T, N, K, g, q, "bf16", workspace=workspace, twin=twin)
+
+
+def test_grouped_streaming_equals_rowwise_streaming_when_scales_repeat(bcq, oracle):
+    """Group-wise scales that repeat one value per row must give the row-wise result of the same kernels
+    (forward and input gradient); the scale gradient summed over the groups must equal the row-wise one."""
+    import torch
+    T, N, K, g, q = 8, 256, 2048, 512, 3
+    W, alpha, planes, packed, x, dy = make_case(3, "out", T, N, K, q, "bf16", oracle)
+    d_packed, d_x, d_dy = packed_to_dev(packed), to_dev(x, "bf16"), to_dev(dy, "bf16")
+    d_twin = bcq.bcq_pack_transposed(d_packed)
+    a_row = to_dev(alpha[:, :, None])
+    a_grp = to_dev(np.repeat(alpha[:, :, None], K // g, axis=2))
+    y_r = bcq.bcq_linear_fwd_grouped(d_packed, a_row, d_x, K, workspace=_ws(bcq, 1, T, N, K, K, q, 1))
+    y_g = bcq.bcq_linear_fwd_grouped(d_packed, a_grp, d_x, g, workspace=_ws(bcq, 1, T, N, K, g, q, 1))
+    dx_r = bcq.bcq_linear_bwd_input_grouped(d_packed, a_row, d_dy, K, packed_t=d_twin,
+                                            workspace=_ws(bcq, 2, T, N, K, K, q, 1))
+    dx_g = bcq.bcq_linear_bwd_input_grouped(d_packed, a_grp, d_dy, g, packed_t=d_twin,
+                                            workspace=_ws(bcq, 2, T, N, K, g, q, 1))
+    da_r = bcq.bcq_linear_bwd_alpha_grouped(d_packed, d_x, d_dy, K, workspace=_ws(bcq, 3, T, N, K, K, q, 1))
+    da_g = bcq.bcq_linear_bwd_alpha_grouped(d_packed, d_x, d_dy, g, workspace=_ws(bcq, 3, T, N, K, g, q, 1))
+    _sync()
+    tol = tol_for("bf16")
+    assert nmax_err(to_host(y_g), to_host(y_r)) <= tol
+    assert torch.equal(dx_g, dx_r)  # same re-coded activations per plane, same order of sums
+    assert nmax_err(to_host(da_g).sum(axis=2), to_host(da_r)[:, :, 0]) <= 1e-5
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
