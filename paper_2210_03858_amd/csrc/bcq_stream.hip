@@ -39,7 +39,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 q_bf16x2;
 
 enum { STREAM_FWD = 0, STREAM_DALPHA = 1, STREAM_DX = 2 };
 
-constexpr int QBLK = 2048;   // bytes of one FP8 operand: 64 lanes x 32 B
+constexpr int QBLK = 2048;   // bytes of one FP8 operand: 2 register halves x 64 lanes x 16 B
 constexpr int QSCL = 256;    // bytes of the scales of one segment and half: 64 lanes x 4 instructions
 
 struct StreamPlan {
@@ -130,7 +130,8 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
             t2[pr >> 1] |= (uint32_t)p2 << 16;
         }
     }
-    // chunk 2 G + cc (cc = 0, 1) lives in lane group (2 G + cc) % 4, bytes 16 ((2 G + cc) / 4) .. + 15
+    // chunk 2 G + cc (cc = 0, 1) lives in lane group (2 G + cc) % 4, register half (2 G + cc) / 4; an operand block is
+    // stored as [register half][lane][16 B], so that a 16-byte read per lane is contiguous over the wave
     const int col1 = tl, col2 = one_half ? tl + 8 : tl;
     const int half2 = one_half ? 0 : 1;
     if (one_half && tl >= 8) return;  // columns 8 .. 15 of the single half belong to the second term of tokens 0 .. 7
@@ -140,8 +141,8 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
         const int c = 2 * G + cc, gB = c & 3, hh = c >> 2;
         const q_u32x4 o1 = {t1[4 * cc], t1[4 * cc + 1], t1[4 * cc + 2], t1[4 * cc + 3]};
         const q_u32x4 o2 = {t2[4 * cc], t2[4 * cc + 1], t2[4 * cc + 2], t2[4 * cc + 3]};
-        *reinterpret_cast<q_u32x4*>(xq + (blk + 0) * QBLK + (gB * 16 + col1) * 32 + 16 * hh) = o1;
-        *reinterpret_cast<q_u32x4*>(xq + (blk + half2) * QBLK + (gB * 16 + col2) * 32 + 16 * hh) = o2;
+        *reinterpret_cast<q_u32x4*>(xq + (blk + 0) * QBLK + hh * (QBLK / 2) + (gB * 16 + col1) * 16) = o1;
+        *reinterpret_cast<q_u32x4*>(xq + (blk + half2) * QBLK + hh * (QBLK / 2) + (gB * 16 + col2) * 16) = o2;
     }
     const size_t sblk = (size_t)(tile * segs + seg) * halves;
     sq[(sblk + 0) * QSCL + (col1 + 16 * G) * 4 + j] = (unsigned char)sb1;
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
         xqp[ps] = xq + (size_t)pc * xq_plane + (size_t)tile * segs * 4 * H * QBLK;
         sqp[ps] = sq + (size_t)pc * sq_plane + (size_t)tile * segs * H * QSCL;
     }
-    const uint32_t lane32 = (uint32_t)lane * 32u, lane4 = (uint32_t)lane * 4u;
+    const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
 
     // Software pipeline: the plane words of the NEXT segment and the activation operand of the NEXT instruction
     // group are requested before the matrix instructions of the current one are issued.
@@ -272,8 +273,8 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 const unsigned char* bp = xqp[ps] + (uint32_t)(((seg * 4 + jj) * H + h) * QBLK);
-                const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp + lane32);
-                const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + lane32 + 16u);
+                const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp + lane16);
+                const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + lane16 + (uint32_t)(QBLK / 2));
                 bop[buf][ps][h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
                                           (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
             }
@@ -500,6 +501,328 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// Forward / scale gradient for plane matrices with many rows: the activation operand goes through LDS.
+// A compute unit keeps a limited number of cache misses in flight, and in stream_kernel most of them fetch the
+// re-coded activations (the same bytes for every row tile) instead of sign planes.  Here a workgroup of 8 waves
+// covers RW = 8 / KW row tiles x KW parts of the contraction axis; the activations of LCS segments per part are
+// copied global -> registers -> LDS once per workgroup (double buffered, one barrier per LCS segments) and every
+// wave reads its operand from there, so the misses in flight are almost all sign planes.  The plane words sit in a
+// ring of LCS register sets addressed by the unrolled position, LCS - 1 segments ahead of the multiplication (a
+// register move would have to wait for the load it copies).  Needs cw % 4 == 0.
+// EXACT: every part has spp segments and spp % LCS == 0 - no guards in the loop.
+constexpr int LCS = 4;
+
+template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT>
+__global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restrict__ planes,
+                                                          const unsigned char* __restrict__ xq,
+                                                          const unsigned char* __restrict__ sq,
+                                                          const float* __restrict__ alpha,
+                                                          const bf16_t* __restrict__ dy, void* __restrict__ out,
+                                                          int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
+                                                          int spp, int64_t segs, int gsegs, int G) {
+    static_assert(MODE != STREAM_DX, "forward and scale gradient only");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int H = TWO ? 2 : 1, RW = 8 / KW, PF = LCS - 1;
+    constexpr int XPART = LCS * 4 * H * QBLK, XBUF = KW * XPART;  // operand blocks of one part / of one buffer
+    constexpr int SPART = LCS * H * QSCL, SBUF = KW * SPART;      // scales
+    constexpr int BUFB = XBUF + SBUF;
+    constexpr int NIT = XBUF / (512 * 16);  // 16-byte units per thread and chunk (= KW LCS H)
+    constexpr int NSU = SBUF / 16;          // threads that copy one 16-byte unit of scales
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kp = wave / RW, rtile = wave % RW;
+    const int rl = lane & 15, g = lane >> 4;
+    const int64_t row0 = ((int64_t)blockIdx.x * RW + rtile) * 16;
+    const int64_t tile = blockIdx.y;
+    const int64_t t0 = tile * 16;
+
+    q_f32x4 acc[QP];
+#pragma unroll
+    for (int i = 0; i < QP; ++i) acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint32_t cw32 = (uint32_t)cw;
+    uint32_t roff;
+    {
+        int64_t rr = row0 + rl;
+        rr = rr < rows ? rr : rows - 1;  // rows beyond the matrix give outputs that are never stored
+        roff = (uint32_t)(rr * cw);
+    }
+    const int64_t plane_stride = rows * cw;
+    const uint32_t* pl[QP];
+#pragma unroll
+    for (int i = 0; i < QP; ++i) pl[i] = planes + (int64_t)(i < q_used ? i : q_used - 1) * plane_stride;
+
+    const int tcol = TWO ? rl : (rl & 7);
+    const bool tok_live = (t0 + tcol) < T;
+    const int64_t tok = tok_live ? t0 + tcol : T - 1;
+    float ep[QP][4];  // FWD: alpha_i of this lane's 4 rows; DALPHA: dy of this lane's token and 4 rows (slot 0)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        int64_t n = row0 + 4 * g + v;
+        const bool n_live = n < rows;
+        n = n_live ? n : rows - 1;
+        if (MODE == STREAM_FWD) {
+#pragma unroll
+            for (int i = 0; i < QP; ++i) ep[i][v] = (!GROUPED && i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+        } else {
+            ep[0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
+        }
+    }
+
+    const unsigned char* xqt = xq + (size_t)tile * segs * 4 * H * QBLK;
+    const unsigned char* sqt = sq + (size_t)tile * segs * H * QSCL;
+    const int part_begin = kp * spp;
+    int part_end = part_begin + spp;
+    part_end = part_end < (int)segs ? part_end : (int)segs;
+    const bool part_live = EXACT || part_begin < part_end;
+    const int nchunks = (spp + LCS - 1) / LCS;
+    const int last_seg = (int)segs - 1;
+
+    // staging: chunk c of every part, global -> registers -> LDS buffer
+    q_u32x4 stg[NIT], stgs;
+    auto stage_load = [&](int c) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int p = it / (LCS * H), r = it % (LCS * H);  // part, 8 KiB slab of its chunk
+            int seg = p * spp + c * LCS + r / H;
+            if (!EXACT) seg = seg < last_seg ? seg : last_seg;  // in bounds; segments beyond a part are never multiplied
+            stg[it] = *reinterpret_cast<const q_u32x4*>(xqt + (size_t)seg * (4 * H * QBLK) + (r % H) * 8192 + tid * 16);
+        }
+        if (tid < NSU) {
+            const int p = tid / (LCS * H * 16), r2 = tid % (LCS * H * 16);
+            int seg = p * spp + c * LCS + r2 / (H * 16);
+            if (!EXACT) seg = seg < last_seg ? seg : last_seg;
+            stgs = *reinterpret_cast<const q_u32x4*>(sqt + (size_t)seg * (H * QSCL) + (r2 % (H * 16)) * 16);
+        }
+    };
+    auto stage_store = [&](int buf) {
+        unsigned char* b = lds + buf * BUFB;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) *reinterpret_cast<q_u32x4*>(b + it * 8192 + tid * 16) = stg[it];
+        if (tid < NSU) *reinterpret_cast<q_u32x4*>(b + XBUF + tid * 16) = stgs;
+    };
+
+    uint32_t bits[LCS][QP][4];
+    auto load_bits = [&](int seg, int slot) {
+        uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
+        w0 = w0 < cw32 - 4u ? w0 : cw32 - 4u;  // a segment that reaches beyond the row is shifted back inside it
+#pragma unroll
+        for (int i = 0; i < QP; ++i) {
+            const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(pl[i] + (roff + w0));
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) bits[slot][i][jj] = v4[jj];
+        }
+    };
+
+    q_f32x4 yv = {0.f, 0.f, 0.f, 0.f};
+    float ga[QP][4];
+    auto load_group_alpha = [&](int grp) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            int64_t n = row0 + 4 * g + v;
+            n = n < rows ? n : rows - 1;
+#pragma unroll
+            for (int i = 0; i < QP; ++i) ga[i][v] = (i < q_used) ? alpha[((int64_t)i * rows + n) * G + grp] : 0.f;
+        }
+    };
+
+    stage_load(0);
+    if (part_live) {
+#pragma unroll
+        for (int d = 0; d < PF; ++d) {
+            const int sg = part_begin + d;
+            load_bits(EXACT ? sg : (sg < part_end ? sg : part_end - 1), d);
+        }
+    }
+    stage_store(0);
+    __syncthreads();
+
+#pragma unroll 1
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        stage_load(c + 1 < nchunks ? c + 1 : c);  // after the last chunk: re-requests it (unused)
+        const unsigned char* xb = lds + buf * BUFB + kp * XPART;
+        const unsigned char* sb = lds + buf * BUFB + XBUF + kp * SPART;
+#pragma unroll
+        for (int s = 0; s < LCS; ++s) {
+            const int seg = part_begin + c * LCS + s;  // its planes sit in ring set s
+            asm volatile("" ::: "memory");  // keeps the loads of the four unrolled segments where they are written
+            if (part_live) {
+                const int pseg = seg + PF;
+                load_bits(pseg < part_end ? pseg : part_end - 1, (s + PF) % LCS);  // beyond the part: unused
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (EXACT || seg < part_end) {  // uniform per wave
+                if (GROUPED && MODE == STREAM_FWD && (seg == part_begin || seg % gsegs == 0)) load_group_alpha(seg / gsegs);
+                int sv[H];
+#pragma unroll
+                for (int h = 0; h < H; ++h) sv[h] = *reinterpret_cast<const int*>(sb + (s * H + h) * QSCL + lane * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    q_i32x8 bo[H];
+#pragma unroll
+                    for (int h = 0; h < H; ++h) {
+                        const unsigned char* bp = xb + ((s * 4 + j) * H + h) * QBLK + lane * 16;
+                        const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp);
+                        const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + QBLK / 2);
+                        bo[h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
+                                        (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                    }
+#pragma unroll
+                    for (int i = 0; i < QP; ++i) {
+                        const uint32_t wd = bits[s][i][j];
+                        q_i32x8 aop;
+#pragma unroll
+                        for (int sft = 0; sft < 4; ++sft) aop[sft] = (int)(((wd << sft) & 0x88888888u) ^ 0xAAAAAAAAu);
+                        aop[4] = 0;
+                        aop[5] = 0;
+                        aop[6] = 0;
+                        aop[7] = 0;
+#pragma unroll
+                        for (int h = 0; h < H; ++h) {
+                            // the instruction picks byte j of the scale register (its op_sel): j must be a constant
+                            if (j == 0)
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 0, sv[h]);
+                            else if (j == 1)
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 1, sv[h]);
+                            else if (j == 2)
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 2, sv[h]);
+                            else
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 3, sv[h]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // pins the matrix instructions of this segment before the loads of the next (they are no memory
+                // operations, so the barrier above alone lets the optimiser sink them to the end of the chunk)
+#pragma unroll
+                for (int i = 0; i < QP; ++i) asm volatile("" : "+v"(acc[i]));
+                if (GROUPED && ((seg + 1) % gsegs == 0 || seg + 1 == part_end)) {  // uniform: a scale group ends
+                    const int grp = seg / gsegs;
+                    if (MODE == STREAM_FWD) {
+#pragma unroll
+                        for (int i = 0; i < QP; ++i)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) yv[v] += ga[i][v] * acc[i][v];
+                    } else {
+                        // both columns of a token (t and t + 8 with one half) carry dy of that token: the 16-lane sum
+                        // adds the two terms and the tokens at once
+                        const int64_t n = row0 + 4 * g;
+#pragma unroll
+                        for (int o = 0; o < QP; ++o)
+                            if (o < q_used) {
+                                q_f32x4 sum;
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) {
+                                    float x = ep[0][v] * acc[o][v];
+                                    x += __shfl_xor(x, 1);
+                                    x += __shfl_xor(x, 2);
+                                    x += __shfl_xor(x, 4);
+                                    x += __shfl_xor(x, 8);
+                                    sum[v] = x * scale;
+                                }
+                                if (rl == 0)
+#pragma unroll
+                                    for (int v = 0; v < 4; ++v)
+                                        if (n + v < rows)
+                                            reinterpret_cast<float*>(out)[(((int64_t)o * rows + n + v) * G) + grp] = sum[v];
+                            }
+                    }
+#pragma unroll
+                    for (int i = 0; i < QP; ++i) acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+        stage_store(buf ^ 1);
+        __syncthreads();  // chunk c + 1 is visible; everyone is done reading chunk c
+    }
+
+    if (GROUPED && MODE == STREAM_DALPHA) return;  // every group was stored at its end
+    if (GROUPED && MODE == STREAM_FWD) {            // continue below with y in place of the plane sums
+        acc[0] = yv;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ep[0][v] = 1.f;
+#pragma unroll
+        for (int i = 1; i < QP; ++i) {
+            acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ep[i][v] = 0.f;
+        }
+    }
+    if (!TWO) {  // one half: add the second term's columns (t + 8) onto the first term's (t)
+#pragma unroll
+        for (int i = 0; i < QP; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][v] += __shfl_xor(acc[i][v], 8);
+    }
+    constexpr int NOUT = (MODE == STREAM_DALPHA) ? QP : 1;
+    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
+    q_f32x4 part[NOUT];
+    if (MODE == STREAM_FWD) {
+        q_f32x4 y = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < QP; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) y[v] += ep[i][v] * acc[i][v];  // alpha of unused planes is 0
+        part[0] = y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < NOUT; ++i) part[i] = acc[i];
+    }
+    if (KW > 1) {  // sum over the parts in part order (the staging buffers are free after the last barrier)
+        float* red = reinterpret_cast<float*>(lds);
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout && kp > 0) *reinterpret_cast<q_f32x4*>(&red[(((kp * RW + rtile) * nout + o) * 64 + lane) * 4]) = part[o];
+        __syncthreads();
+        if (kp != 0) return;
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout) {
+                q_f32x4 sum = part[o];
+                for (int w = 1; w < KW; ++w)
+                    sum += *reinterpret_cast<const q_f32x4*>(&red[(((w * RW + rtile) * nout + o) * 64 + lane) * 4]);
+                part[o] = sum;
+            }
+    }
+    const bool col_live = tok_live && (TWO || rl < 8);  // with one half, columns 8 .. 15 duplicate columns 0 .. 7
+    const int64_t n = row0 + 4 * g;                     // first of this lane's 4 rows
+    if (MODE == STREAM_DALPHA) {
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout) {
+                q_f32x4 sum;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float x = col_live ? ep[0][v] * part[o][v] : 0.f;
+                    x += __shfl_xor(x, 1);
+                    x += __shfl_xor(x, 2);
+                    x += __shfl_xor(x, 4);
+                    x += __shfl_xor(x, 8);
+                    sum[v] = x * scale;
+                }
+                if (rl == 0)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (n + v < rows) reinterpret_cast<float*>(out)[(int64_t)o * rows + n + v] = sum[v];
+            }
+    } else {
+        bf16_t* o = reinterpret_cast<bf16_t*>(out);
+        if (col_live) {
+            if (n + 3 < rows && (rows & 3) == 0) {
+                q_u32x2 pk;
+                pk[0] = q_pack_bf16x2(part[0][0], part[0][1]);
+                pk[1] = q_pack_bf16x2(part[0][2], part[0][3]);
+                *reinterpret_cast<q_u32x2*>(o + tok * rows + n) = pk;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (n + v < rows) o[tok * rows + n + v] = f32_to_bf16(part[0][v]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // gsegs > 0: the contraction axis carries scale groups of gsegs segments each and every wave must own whole groups
 static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw, int gsegs = 0) {
     StreamPlan p;
@@ -553,6 +876,96 @@ size_t stream_workspace(int64_t T, int64_t contraction, int sets) {
     return (size_t)sets * (p.xq_bytes + p.sq_bytes);
 }
 
+// Plan of stream_lds_kernel: KW = 0 means "use stream_kernel".  It pays when the workgroups (8 / KW row tiles each)
+// still fill the chip, i.e. for plane matrices with many rows.
+struct LdsPlan {
+    int KW, spp;
+    bool exact;
+    unsigned grid_x;
+};
+static LdsPlan lds_plan(int64_t rows, int64_t segs, int halves, int gsegs, int q_used) {
+    LdsPlan p = {0, 0, false, 0};
+    if (q_used > 4) return p;  // the ring of plane registers is sized for up to 4 planes
+    const int64_t rt = (rows + 15) / 16;
+    int kw = 0;
+    if ((rt + 7) / 8 >= 224)
+        kw = 1;
+    else if (halves == 1 && (rt + 3) / 4 >= 224)
+        kw = 2;
+#ifdef BCQ_PROBE_PLAN
+    if (getenv("BCQ_LDS")) kw = atoi(getenv("BCQ_LDS"));
+    if (kw == 2 && halves != 1) kw = 0;
+#endif
+    if (kw == 0 || segs < 2 * LCS * kw) return p;
+    int64_t spp = (segs + kw - 1) / kw;
+    if (gsegs > 0) spp = (spp + gsegs - 1) / gsegs * gsegs;  // whole scale groups per part
+    p.KW = kw;
+    p.spp = (int)spp;
+    p.exact = (spp * kw == segs) && (spp % LCS == 0);
+    p.grid_x = (unsigned)((rt + (8 / kw) - 1) / (8 / kw));
+    return p;
+}
+
+template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT>
+static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq,
+                                 const float* alpha, const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw,
+                                 int q_used, float scale, const LdsPlan& lp, int64_t segs, int tiles, int gsegs, int G,
+                                 hipStream_t st) {
+    constexpr int H = TWO ? 2 : 1;
+    constexpr int LDS_B = 2 * KW * LCS * H * (4 * QBLK + QSCL);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_B);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
+                       LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G);
+    return hipGetLastError();
+}
+
+template <int MODE, int QP, bool TWO, bool GROUPED>
+static hipError_t launch_lds_kw(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq,
+                                const float* alpha, const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw,
+                                int q_used, float scale, const LdsPlan& lp, int64_t segs, int tiles, int gsegs, int G,
+                                hipStream_t st) {
+#define BCQ_LDS_GO(KW, EX) \
+    return launch_lds_cfg<MODE, QP, TWO, GROUPED, KW, EX>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, \
+                                                          segs, tiles, gsegs, G, st)
+    if (!TWO && lp.KW == 2) {
+        if (lp.exact) BCQ_LDS_GO((TWO ? 1 : 2), true);
+        BCQ_LDS_GO((TWO ? 1 : 2), false);
+    }
+    if (lp.exact) BCQ_LDS_GO(1, true);
+    BCQ_LDS_GO(1, false);
+#undef BCQ_LDS_GO
+}
+
+template <int MODE>
+static hipError_t launch_lds(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq, const float* alpha,
+                             const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
+                             const LdsPlan& lp, int64_t segs, int tiles, int halves, bool grouped, int gsegs, int G,
+                             hipStream_t st) {
+#define BCQ_LDS_ARGS planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, segs, tiles, gsegs, G, st
+#define BCQ_LDS_Q(QQ)                                                                          \
+    if (halves == 2) {                                                                         \
+        if (grouped) return launch_lds_kw<MODE, QQ, true, true>(BCQ_LDS_ARGS);                 \
+        return launch_lds_kw<MODE, QQ, true, false>(BCQ_LDS_ARGS);                             \
+    } else {                                                                                   \
+        if (grouped) return launch_lds_kw<MODE, QQ, false, true>(BCQ_LDS_ARGS);                \
+        return launch_lds_kw<MODE, QQ, false, false>(BCQ_LDS_ARGS);                            \
+    }
+    switch (q_used) {
+        case 1: BCQ_LDS_Q(1)
+        case 2: BCQ_LDS_Q(2)
+        case 3: BCQ_LDS_Q(3)
+        default: BCQ_LDS_Q(4)
+    }
+#undef BCQ_LDS_Q
+#undef BCQ_LDS_ARGS
+}
+
 // g = group size of the scales along the columns of W (K of the layer); g == layer K means row-wise.
 template <int MODE>
 static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
@@ -573,6 +986,14 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
                            p.tiles, xq, sq, p.xq_bytes, p.sq_bytes, G);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+    }
+    if constexpr (MODE != STREAM_DX) {
+        if (cw % 4 == 0) {
+            const LdsPlan lp = lds_plan(rows, p.segs, p.halves, gsegs, q_used);
+            if (lp.KW > 0)
+                return launch_lds<MODE>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, p.segs, p.tiles,
+                                        p.halves, grouped, gsegs > 0 ? gsegs : 1, G, st);
+        }
     }
     const dim3 grid(p.grid_x, (unsigned)p.tiles);
     const dim3 block((unsigned)(64 * p.W));

@@ -146,6 +146,37 @@ def test_grouped_small_token_streaming_parity(bcq, oracle, T, N, K, g, q):
         _run_layer(bcq, oracle, 3, "out", T, N, K, g, q, "bf16", workspace=workspace, twin=twin)
 
 
+MANY_ROWS = [
+    # plane matrices with many rows: the workgroups share the re-coded activations through LDS
+    # T, N, K, g, q
+    (8, 14336, 4096, 4096, 4),    # two parts of the contraction axis, whole chunks: guard-free instantiation
+    (5, 14352, 4608, 4608, 3),    # ragged rows, 9 segments over two parts (5 + 4): guarded instantiation
+    (8, 14336, 4096, 1024, 4),    # group-wise scales, two segments per group
+    (3, 14400, 6144, 1536, 2),    # three-segment groups: parts of 6 segments, chunks straddle groups
+    (12, 28672, 4096, 4096, 4),   # two register halves per token tile (9 .. 16 tokens): one part, 8 row tiles
+    (16, 28688, 4608, 512, 1),    # the same with group-wise scales and ragged rows
+    (1, 14336, 4096 + 32, 4128, 4),  # K / 32 not a multiple of 4: falls back to the per-wave kernel
+]
+
+
+@pytest.mark.parametrize("T,N,K,g,q", MANY_ROWS)
+def test_many_rows_streaming_parity(bcq, oracle, T, N, K, g, q):
+    """Forward and scale gradient (the input gradient of these shapes streams a plane matrix with few rows)."""
+    W, alpha, planes, packed, x, dy = make_case(3, "mlp_up", T, N, K, q, "bf16", oracle, g=g)
+    if alpha.ndim == 2:
+        alpha = alpha[:, :, None]
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha)
+    d_x, d_dy = to_dev(x, "bf16"), to_dev(dy, "bf16")
+    y = bcq.bcq_linear_fwd_grouped(d_packed, d_alpha, d_x, g, workspace=_ws(bcq, 1, T, N, K, g, q, 1))
+    da = bcq.bcq_linear_bwd_alpha_grouped(d_packed, d_x, d_dy, g, workspace=_ws(bcq, 3, T, N, K, g, q, 1))
+    _sync()
+    tol = tol_for("bf16")
+    a_or = alpha if g != K else alpha[:, :, 0]
+    ref_da = oracle.bwd_alpha(planes, x, dy, g=g)
+    assert nmax_err(to_host(y), oracle.fwd(a_or, planes, x)) <= tol
+    assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
+
+
 def test_grouped_streaming_equals_rowwise_streaming_when_scales_repeat(bcq, oracle):
     """Group-wise scales that repeat one value per row must give the row-wise result of the same kernels
     (forward and input gradient); the scale gradient summed over the groups must equal the row-wise one."""
