@@ -33,8 +33,9 @@ PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.7
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # a step is about half a millisecond: the defaults time 50 ms of steady state after the clocks have settled
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=2, help="workload number (2 = GPT-2-medium block, the headline)")
     ap.add_argument("--tokens", type=int, default=0, help="override the token count of the workload")
     ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
