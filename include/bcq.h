@@ -75,7 +75,8 @@ typedef enum {
 /* Static, NUL-terminated description of a status code. */
 const char* bcq_status_string(bcq_status s);
 
-/* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points). */
+/* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points;
+ * 5: decode layout). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -130,6 +131,26 @@ bcq_status bcq_unpack(const uint32_t* packed, int64_t N, int64_t K, int q, int8_
  * bits running along N).  Needs N % 32 == 0.  One-time, like bcq_pack; used by bcq_linear_bwd_input. */
 bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* packed_t,
                                void* stream);
+
+/* Decode layout of the sign planes (Section 3 ends with inference through kernels that multiply by the packed binary
+ * codes directly instead of dequantising; this is the layout our small-token forward streams fastest): the same bits
+ * as the canonical layout, tile-ordered so that every 4 KiB a wave reads is one contiguous run in HBM.
+ *   tiled [ceil(N/16)][ceil(K/512)][q][64][4] uint32: row tile rt, 512-column segment seg, plane i, lane l, word j
+ *   hold canonical word packed[i][16 rt + l % 16][16 seg + 4 (l / 16) + j]; rows >= N and words >= K/32 read as 0.
+ * bcq_decode_layout_bytes gives the size of `tiled`; bcq_pack_decode builds it (one-time, like bcq_pack). */
+bcq_status bcq_decode_layout_bytes(int64_t N, int64_t K, int q, size_t* out);
+bcq_status bcq_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, void* stream);
+
+/* Forward (Eq. 2) from the decode layout, for fewer than 32 tokens of bf16 activations: same result as
+ * bcq_linear_fwd_grouped on the canonical planes.
+ *   tiled: output of bcq_pack_decode, in; alpha [q][N][K/g] fp32 in (g == K: row-wise; else g % 512 == 0);
+ *   x [T][K] bf16 in; y [T][N] bf16 out; workspace REQUIRED, at least
+ *   bcq_workspace_bytes_grouped(BCQ_OP_FWD, T, N, K, g, q, BCQ_BF16) bytes.
+ * Errors: BCQ_ERR_DTYPE for fp32 activations; BCQ_ERR_SHAPE for T >= 32 or a group size the streaming kernels do
+ * not take; BCQ_ERR_NULL without workspace; the others as for bcq_linear_fwd. */
+bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, const void* x, int dtype, int64_t T,
+                                 int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
+                                 size_t workspace_bytes, void* stream);
 
 /* Forward (Eq. 2): y[t][n] = sum_i alpha_i[n] * sum_k B_i[n][k] * x[t][k], fp32 accumulation,
  * result rounded to `dtype` (bf16: round to nearest even).  The dequantised W exists at most as a transient bf16

@@ -21,7 +21,8 @@ EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_q
            "bcq_unpack", "bcq_pack_transposed", "bcq_linear_fwd", "bcq_linear_bwd_input", "bcq_linear_bwd_alpha",
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
            "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
-           "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw")
+           "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw", "bcq_decode_layout_bytes", "bcq_pack_decode",
+           "bcq_linear_fwd_decode")
 
 _lib = None
 
@@ -69,6 +70,9 @@ def load():
     lib.bcq_alpha_adamw_step.argtypes = [vp, vp, vp, vp, i64, ap, vp]
     lib.bcq_linear_bwd_alpha_adamw.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, i32, f32, vp, vp, vp, vp, ap,
                                                vp, sz, vp]
+    lib.bcq_decode_layout_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(sz)]
+    lib.bcq_pack_decode.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.bcq_linear_fwd_decode.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -180,6 +184,43 @@ def bcq_pack_transposed(packed, packed_t=None):
         packed_t = torch.empty((q, K, max(N // 32, 1)), dtype=torch.int32, device=packed.device)
     _check(load().bcq_pack_transposed(_ptr(packed), N, K, q, _ptr(packed_t), _stream()), "bcq_pack_transposed")
     return packed_t
+
+
+def decode_layout_bytes(N, K, q):
+    out = ctypes.c_size_t(0)
+    _check(load().bcq_decode_layout_bytes(N, K, q, ctypes.byref(out)), "bcq_decode_layout_bytes")
+    return int(out.value)
+
+
+def bcq_pack_decode(packed, tiled=None):
+    """canonical packed[q,N,K/32] -> decode layout (flat int32 tensor of decode_layout_bytes(N, K, q) bytes)."""
+    q, N, Kw = packed.shape
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    K = Kw * 32
+    words = decode_layout_bytes(N, K, q) // 4
+    if tiled is None:
+        tiled = torch.empty((words,), dtype=torch.int32, device=packed.device)
+    _need(tiled, torch.int32, (words,), "tiled")
+    _check(load().bcq_pack_decode(_ptr(packed), N, K, q, _ptr(tiled), _stream()), "bcq_pack_decode")
+    return tiled
+
+
+def bcq_linear_fwd_decode(tiled, alpha, x, g=None, y=None, workspace=None):
+    """Forward from the decode layout; alpha[q,N] or [q,N,K/g]; fewer than 32 tokens of bf16; workspace required."""
+    T, K = x.shape
+    q, N = alpha.shape[0], alpha.shape[1]
+    g = K if g is None else int(g)
+    dt = _act_dtype(x)
+    _need(tiled, torch.int32, (decode_layout_bytes(N, K, q) // 4,), "tiled")
+    if alpha.dim() == 2:
+        alpha = alpha.reshape(q, N, 1)
+    _need(alpha, torch.float32, (q, N, K // max(g, 1)), "alpha")
+    y = torch.empty((T, N), dtype=x.dtype, device=x.device) if y is None else y
+    _need(y, x.dtype, (T, N), "y")
+    wp, wb = _ws(workspace)
+    _check(load().bcq_linear_fwd_decode(_ptr(tiled), _ptr(alpha), _ptr(x), dt, T, N, K, g, q, _ptr(y), wp, wb,
+                                        _stream()), "bcq_linear_fwd_decode")
+    return y
 
 
 def bcq_linear_fwd(packed, alpha, x, y=None, workspace=None):

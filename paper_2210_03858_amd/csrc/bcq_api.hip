@@ -128,7 +128,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 4; }
+int bcq_abi_version(void) { return 5; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {
@@ -248,6 +248,42 @@ bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, co
     if (workspace && mfma_fwd_ok(T, rowwise, dtype))
         return done(bcq::launch_fwd_mfma(packed, alpha, x, T, N, K, g, q, y, workspace, st));
     return done(bcq::launch_fwd_generic(packed, alpha, x, dtype, T, N, K, g, q, y, st));
+}
+
+bcq_status bcq_decode_layout_bytes(int64_t N, int64_t K, int q, size_t* out) {
+    if (!out) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    *out = bcq::decode_layout_bytes(N, K, q);
+    return BCQ_OK;
+}
+
+bcq_status bcq_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, void* stream) {
+    if (!packed || !tiled) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(1, N, K, q);
+    if (s != BCQ_OK) return s;
+    if (misaligned(packed) || misaligned(tiled)) return BCQ_ERR_ALIGN;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_pack_decode(packed, N, K, q, tiled, (hipStream_t)stream));
+}
+
+bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, const void* x, int dtype, int64_t T,
+                                 int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!tiled || !alpha || !x || !y || !workspace) return BCQ_ERR_NULL;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
+    if (dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    if (!stream_fwd_ok(T, K, g, dtype)) return BCQ_ERR_SHAPE;  // fewer than 32 tokens; row-wise or g % 512 == 0
+    if (misaligned(tiled) || misaligned(alpha) || misaligned(x) || misaligned(y)) return BCQ_ERR_ALIGN;
+    s = check_workspace(workspace, workspace_bytes, bcq::stream_fwd_workspace(T, K));
+    if (s != BCQ_OK) return s;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    return done(bcq::launch_fwd_stream_decode(tiled, alpha, x, T, N, K, g, q, y, workspace, (hipStream_t)stream));
 }
 
 bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,

@@ -102,6 +102,10 @@ size_t stream_bwd_alpha_workspace(int64_t T, int64_t K);
 size_t stream_bwd_input_workspace(int64_t T, int64_t N, int sets /* q * (K / g) */);
 hipError_t launch_fwd_stream(const uint32_t* packed, const float* alpha, const void* x, int64_t T, int64_t N,
                              int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st);
+hipError_t launch_fwd_stream_decode(const uint32_t* tiled, const float* alpha, const void* x, int64_t T, int64_t N,
+                                    int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st);
+size_t decode_layout_bytes(int64_t N, int64_t K, int q);
+hipError_t launch_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, hipStream_t st);
 hipError_t launch_bwd_alpha_stream(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                    int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
                                    void* workspace, hipStream_t st);

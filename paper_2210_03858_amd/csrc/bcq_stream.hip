@@ -158,7 +158,9 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
 // every group boundary (gsegs segments).  Scale gradient: every group's sums are reduced over the tokens and stored
 // at its end; the host gives every wave whole groups, so no cross-wave sum is needed.  Input gradient: the set of
 // re-coded activations is chosen by the group of the workgroup's rows (dxg rows of the twin per group).
-template <int MODE, int R, int QP, bool TWO, bool QUAD, bool GROUPED>
+// TILED (forward only): `planes` is the decode layout [row tile][segment][plane][64 lanes][4 words] (padded to whole
+// row tiles and segments), so the 1 KiB a wave reads per plane and segment is one contiguous run.
+template <int MODE, int R, int QP, bool TWO, bool QUAD, bool GROUPED, bool TILED>
 __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict__ planes,
                                                       const unsigned char* __restrict__ xq,
                                                       const unsigned char* __restrict__ sq,
@@ -239,7 +241,18 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
     int sc[2][NSET][H];
     auto load_bits = [&](int seg, int buf) {
         uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
-        if (QUAD) {
+        if (TILED) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t* tb = planes + (((row0 >> 4) + r) * segs + seg) * (int64_t)(q_used * 256) + lane * 4;
+#pragma unroll
+                for (int i = 0; i < PPP; ++i) {
+                    const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(tb + (i < q_used ? i : q_used - 1) * 256);
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) bits[buf][r][i][jj] = v4[jj];
+                }
+            }
+        } else if (QUAD) {
             w0 = w0 < cw32 - 4u ? w0 : cw32 - 4u;
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -512,7 +525,18 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
 // EXACT: every part has spp segments and spp % LCS == 0 - no guards in the loop.
 constexpr int LCS = 4;
 
-template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT>
+// 32 signs of a packed word -> the four FP4 operand registers of a lane (+1 = 0x2, -1 = 0xA; registers 4 .. 7 of the
+// builtin's operand type are not part of an FP4 operand)
+__device__ __forceinline__ void expand_one(uint32_t wd, q_i32x8& aop) {
+#pragma unroll
+    for (int sft = 0; sft < 4; ++sft) aop[sft] = (int)(((wd << sft) & 0x88888888u) ^ 0xAAAAAAAAu);
+    aop[4] = 0;
+    aop[5] = 0;
+    aop[6] = 0;
+    aop[7] = 0;
+}
+
+template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT, bool TILED>
 __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restrict__ planes,
                                                           const unsigned char* __restrict__ xq,
                                                           const unsigned char* __restrict__ sq,
@@ -602,7 +626,20 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
     };
 
     uint32_t bits[LCS][QP][4];
+    // decode layout: row tiles beyond the padded matrix (last workgroup) re-read the last one; nothing of them is stored
+    const int64_t rt_pad = (rows + 15) >> 4;
+    const int64_t rt_mine = (row0 >> 4) < rt_pad ? (row0 >> 4) : rt_pad - 1;
     auto load_bits = [&](int seg, int slot) {
+        if (TILED) {
+            const uint32_t* tb = planes + (rt_mine * segs + seg) * (int64_t)(q_used * 256) + lane * 4;
+#pragma unroll
+            for (int i = 0; i < QP; ++i) {
+                const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(tb + (i < q_used ? i : q_used - 1) * 256);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) bits[slot][i][jj] = v4[jj];
+            }
+            return;
+        }
         uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
         w0 = w0 < cw32 - 4u ? w0 : cw32 - 4u;  // a segment that reaches beyond the row is shifted back inside it
 #pragma unroll
@@ -642,6 +679,25 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
         stage_load(c + 1 < nchunks ? c + 1 : c);  // after the last chunk: re-requests it (unused)
         const unsigned char* xb = lds + buf * BUFB + kp * XPART;
         const unsigned char* sb = lds + buf * BUFB + XBUF + kp * SPART;
+        // operand of instruction group (s, j) and scales of segment s, LDS -> registers one group ahead of their use
+        q_i32x8 bo[2][H];
+        int sv[2][H];
+        auto read_b = [&](int s, int j, int slot) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const unsigned char* bp = xb + ((s * 4 + j) * H + h) * QBLK + lane * 16;
+                const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp);
+                const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + QBLK / 2);
+                bo[slot][h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
+                                      (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            }
+        };
+        auto read_s = [&](int s, int slot) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) sv[slot][h] = *reinterpret_cast<const int*>(sb + (s * H + h) * QSCL + lane * 4);
+        };
+        read_s(0, 0);
+        read_b(0, 0, 0);
 #pragma unroll
         for (int s = 0; s < LCS; ++s) {
             const int seg = part_begin + c * LCS + s;  // its planes sit in ring set s
@@ -653,44 +709,42 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
             __builtin_amdgcn_sched_barrier(0);
             if (EXACT || seg < part_end) {  // uniform per wave
                 if (GROUPED && MODE == STREAM_FWD && (seg == part_begin || seg % gsegs == 0)) load_group_alpha(seg / gsegs);
-                int sv[H];
+                // The FP4 operands of instruction group j + 1 are expanded while the matrix instructions of group j
+                // run: each expansion is written right behind one matrix instruction, into registers no instruction
+                // in flight reads (two sets), so the vector ALU works in the shadow of the matrix pipe.
+                q_i32x8 ao[2][QP];
+                auto expand = [&](int j, int set) {
 #pragma unroll
-                for (int h = 0; h < H; ++h) sv[h] = *reinterpret_cast<const int*>(sb + (s * H + h) * QSCL + lane * 4);
+                    for (int i = 0; i < QP; ++i) expand_one(bits[s][i][j], ao[set][i]);
+                };
+                expand(0, 0);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    q_i32x8 bo[H];
-#pragma unroll
-                    for (int h = 0; h < H; ++h) {
-                        const unsigned char* bp = xb + ((s * 4 + j) * H + h) * QBLK + lane * 16;
-                        const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp);
-                        const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + QBLK / 2);
-                        bo[h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3],
-                                        (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                    // group (s, j) sits in slot (4 s + j) % 2 = j % 2; request the next group of this chunk
+                    if (j < 3) {
+                        read_b(s, j + 1, (j + 1) & 1);
+                    } else if (s + 1 < LCS) {
+                        read_b(s + 1, 0, 0);
+                        read_s(s + 1, (s + 1) & 1);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < QP; ++i) {
-                        const uint32_t wd = bits[s][i][j];
-                        q_i32x8 aop;
-#pragma unroll
-                        for (int sft = 0; sft < 4; ++sft) aop[sft] = (int)(((wd << sft) & 0x88888888u) ^ 0xAAAAAAAAu);
-                        aop[4] = 0;
-                        aop[5] = 0;
-                        aop[6] = 0;
-                        aop[7] = 0;
 #pragma unroll
                         for (int h = 0; h < H; ++h) {
                             // the instruction picks byte j of the scale register (its op_sel): j must be a constant
                             if (j == 0)
-                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 0, sv[h]);
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ao[j & 1][i], bo[j & 1][h], acc[i], 4, 0, 0, 127, 0, sv[s & 1][h]);
                             else if (j == 1)
-                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 1, sv[h]);
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ao[j & 1][i], bo[j & 1][h], acc[i], 4, 0, 0, 127, 1, sv[s & 1][h]);
                             else if (j == 2)
-                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 2, sv[h]);
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ao[j & 1][i], bo[j & 1][h], acc[i], 4, 0, 0, 127, 2, sv[s & 1][h]);
                             else
-                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 3, sv[h]);
+                                acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ao[j & 1][i], bo[j & 1][h], acc[i], 4, 0, 0, 127, 3, sv[s & 1][h]);
                         }
+                        if (j < 3) expand_one(bits[s][i][j + 1], ao[(j + 1) & 1][i]);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
                 // pins the matrix instructions of this segment before the loads of the next (they are no memory
                 // operations, so the barrier above alone lets the optimiser sink them to the end of the chunk)
@@ -906,7 +960,7 @@ static LdsPlan lds_plan(int64_t rows, int64_t segs, int halves, int gsegs, int q
     return p;
 }
 
-template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT>
+template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT, bool TILED>
 static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq,
                                  const float* alpha, const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw,
                                  int q_used, float scale, const LdsPlan& lp, int64_t segs, int tiles, int gsegs, int G,
@@ -915,23 +969,23 @@ static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq
     constexpr int LDS_B = 2 * KW * LCS * H * (4 * QBLK + QSCL);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT>,
+        hipError_t e = hipFuncSetAttribute((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_B);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
+    hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
                        LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G);
     return hipGetLastError();
 }
 
-template <int MODE, int QP, bool TWO, bool GROUPED>
+template <int MODE, int QP, bool TWO, bool GROUPED, bool TILED>
 static hipError_t launch_lds_kw(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq,
                                 const float* alpha, const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw,
                                 int q_used, float scale, const LdsPlan& lp, int64_t segs, int tiles, int gsegs, int G,
                                 hipStream_t st) {
 #define BCQ_LDS_GO(KW, EX) \
-    return launch_lds_cfg<MODE, QP, TWO, GROUPED, KW, EX>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, \
+    return launch_lds_cfg<MODE, QP, TWO, GROUPED, KW, EX, TILED>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, \
                                                           segs, tiles, gsegs, G, st)
     if (!TWO && lp.KW == 2) {
         if (lp.exact) BCQ_LDS_GO((TWO ? 1 : 2), true);
@@ -942,7 +996,7 @@ static hipError_t launch_lds_kw(const uint32_t* planes, const unsigned char* xq,
 #undef BCQ_LDS_GO
 }
 
-template <int MODE>
+template <int MODE, bool TILED>
 static hipError_t launch_lds(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq, const float* alpha,
                              const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
                              const LdsPlan& lp, int64_t segs, int tiles, int halves, bool grouped, int gsegs, int G,
@@ -950,11 +1004,11 @@ static hipError_t launch_lds(const uint32_t* planes, const unsigned char* xq, co
 #define BCQ_LDS_ARGS planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, segs, tiles, gsegs, G, st
 #define BCQ_LDS_Q(QQ)                                                                          \
     if (halves == 2) {                                                                         \
-        if (grouped) return launch_lds_kw<MODE, QQ, true, true>(BCQ_LDS_ARGS);                 \
-        return launch_lds_kw<MODE, QQ, true, false>(BCQ_LDS_ARGS);                             \
+        if (grouped) return launch_lds_kw<MODE, QQ, true, true, TILED>(BCQ_LDS_ARGS);          \
+        return launch_lds_kw<MODE, QQ, true, false, TILED>(BCQ_LDS_ARGS);                      \
     } else {                                                                                   \
-        if (grouped) return launch_lds_kw<MODE, QQ, false, true>(BCQ_LDS_ARGS);                \
-        return launch_lds_kw<MODE, QQ, false, false>(BCQ_LDS_ARGS);                            \
+        if (grouped) return launch_lds_kw<MODE, QQ, false, true, TILED>(BCQ_LDS_ARGS);         \
+        return launch_lds_kw<MODE, QQ, false, false, TILED>(BCQ_LDS_ARGS);                     \
     }
     switch (q_used) {
         case 1: BCQ_LDS_Q(1)
@@ -967,7 +1021,7 @@ static hipError_t launch_lds(const uint32_t* planes, const unsigned char* xq, co
 }
 
 // g = group size of the scales along the columns of W (K of the layer); g == layer K means row-wise.
-template <int MODE>
+template <int MODE, bool TILED = false>
 static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
                                 int64_t T, int64_t rows, int64_t cw, int q, int q_used, float scale, void* workspace,
                                 int64_t g, int64_t layer_k, hipStream_t st) {
@@ -988,10 +1042,10 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
         if (e != hipSuccess) return e;
     }
     if constexpr (MODE != STREAM_DX) {
-        if (cw % 4 == 0) {
+        if (TILED || cw % 4 == 0) {
             const LdsPlan lp = lds_plan(rows, p.segs, p.halves, gsegs, q_used);
             if (lp.KW > 0)
-                return launch_lds<MODE>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, p.segs, p.tiles,
+                return launch_lds<MODE, TILED>(planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp, p.segs, p.tiles,
                                         p.halves, grouped, gsegs > 0 ? gsegs : 1, G, st);
         }
     }
@@ -1000,9 +1054,9 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
     const int qp = q_used <= 4 ? q_used : 8;
-    const bool quad = (cw % 4 == 0);
+    const bool quad = TILED || (cw % 4 == 0);  // the decode layout has one instantiation (the flag is unused there)
 #define BCQ_STREAM_GO(QQ, TT, QD, GR)                                                                                  \
-    hipLaunchKernelGGL((stream_kernel<MODE, 1, QQ, TT, QD, GR>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, \
+    hipLaunchKernelGGL((stream_kernel<MODE, 1, QQ, TT, QD, GR, TILED>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, \
                        rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127,                  \
                        gsegs > 0 ? gsegs : 1, G, g)
 #define BCQ_STREAM_GR(QQ, TT, QD)            \
@@ -1015,7 +1069,7 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     if (quad) {                          \
         BCQ_STREAM_GR(QQ, TT, true)      \
     } else {                             \
-        BCQ_STREAM_GR(QQ, TT, false)     \
+        BCQ_STREAM_GR(QQ, TT, TILED)     \
     }
 #define BCQ_STREAM_Q(TT)                              \
     switch (qp) {                                     \
@@ -1045,6 +1099,47 @@ hipError_t launch_fwd_stream(const uint32_t* packed, const float* alpha, const v
                              int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st) {
     return launch_stream<STREAM_FWD>(packed, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, workspace, g, K,
                                      st);
+}
+
+hipError_t launch_fwd_stream_decode(const uint32_t* tiled, const float* alpha, const void* x, int64_t T, int64_t N,
+                                    int64_t K, int64_t g, int q, void* y, void* workspace, hipStream_t st) {
+    return launch_stream<STREAM_FWD, true>(tiled, (const bf16_t*)x, alpha, nullptr, y, T, N, K / 32, q, q, 1.f, workspace,
+                                           g, K, st);
+}
+
+// canonical packed[q][N][K/32] -> decode layout [N/16 up][K/512 up][q][64 lanes][4 words]; lane = (n % 16) + 16 g holds
+// words 16 seg + 4 g .. + 3 of row n; rows and columns beyond the matrix read as 0 bits
+__global__ __launch_bounds__(256) void pack_decode_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t cw,
+                                                          int q, int64_t segs, int64_t units,
+                                                          q_u32x4* __restrict__ tiled) {
+    const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one 16-byte unit of the output
+    if (u >= units) return;
+    const int lane = (int)(u & 63);
+    const int i = (int)((u >> 6) % q);
+    const int64_t ts = (u >> 6) / q;
+    const int64_t seg = ts % segs, rt = ts / segs;
+    const int64_t n = rt * 16 + (lane & 15);
+    const int64_t w0 = seg * 16 + 4 * (lane >> 4);
+    q_u32x4 v = {0u, 0u, 0u, 0u};
+    if (n < N) {
+        const uint32_t* src = packed + ((int64_t)i * N + n) * cw;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            if (w0 + jj < cw) v[jj] = src[w0 + jj];
+    }
+    tiled[u] = v;
+}
+
+size_t decode_layout_bytes(int64_t N, int64_t K, int q) {
+    return (size_t)((N + 15) / 16) * (size_t)((K + 511) / 512) * (size_t)q * 1024;
+}
+
+hipError_t launch_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, hipStream_t st) {
+    const int64_t segs = (K + 511) / 512;
+    const int64_t units = (int64_t)(decode_layout_bytes(N, K, q) / 16);
+    hipLaunchKernelGGL(pack_decode_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, packed, N, K / 32, q, segs,
+                       units, reinterpret_cast<q_u32x4*>(tiled));
+    return hipGetLastError();
 }
 
 hipError_t launch_bwd_alpha_stream(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,

@@ -53,3 +53,15 @@ def make_case(config, kind, T, N, K, q, dtype, oracle, outliers=False, extra=0, 
     x = synth.activations(config, kind, T, K, 1, dtype, extra)
     dy = synth.activations(config, kind, T, N, 2, dtype, extra)
     return W, alpha, planes, oracle.pack(planes), x, dy
+
+
+def decode_layout(packed):
+    """Decode layout of include/bcq.h written out with numpy: [row tile][segment][plane][lane = row + 16 g][word j]
+    holds canonical word packed[i][16 rt + row][16 seg + 4 g + j]; padding reads as 0."""
+    import numpy as np
+    q, N, cw = packed.shape
+    rt, segs = -(-N // 16), -(-cw // 16)
+    pad = np.zeros((q, rt * 16, segs * 16), dtype=np.uint32)
+    pad[:, :N, :cw] = packed
+    a = pad.reshape(q, rt, 16, segs, 4, 4).transpose(1, 3, 0, 4, 2, 5)  # rt, seg, plane, g, row, j
+    return np.ascontiguousarray(a).reshape(-1)

@@ -110,6 +110,26 @@ def test_group_size_errors_before_device(lib):
     assert gw.value > rw.value
 
 
+def test_decode_layout_errors_before_device(lib):
+    q, N, K, T = 3, 100, 1056, 8
+    i64 = ctypes.c_int64
+    out = ctypes.c_size_t(0)
+    assert lib.bcq_decode_layout_bytes(N, K, q, ctypes.byref(out)) == 0
+    assert out.value == 7 * 3 * q * 1024  # ceil(100 / 16) row tiles x ceil(1056 / 512) segments x q KiB
+    assert lib.bcq_decode_layout_bytes(N, 40, q, ctypes.byref(out)) == 2
+    assert lib.bcq_decode_layout_bytes(N, K, q, None) == 1
+    assert lib.bcq_pack_decode(A, N, K, q, None, None) == 1
+    assert lib.bcq_pack_decode(A, N, K, 9, A, None) == 2
+    assert lib.bcq_pack_decode(A + 4, N, K, q, A, None) == 4
+    ws = 1 << 24
+    assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(K), q, A, None, 0, None) == 1       # workspace required
+    assert lib.bcq_linear_fwd_decode(A, A, A, 0, T, N, K, i64(K), q, A, A, ws, None) == 3         # bf16 only
+    assert lib.bcq_linear_fwd_decode(A, A, A, 1, 32, N, K, i64(K), q, A, A, ws, None) == 2        # fewer than 32 tokens
+    assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(96), q, A, A, ws, None) == 2        # g % 512 != 0
+    assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(K), q, A, A, 16, None) == 5         # workspace too small
+    assert lib.bcq_linear_fwd_decode(A, A, A + 2, 1, T, N, K, i64(K), q, A, A, ws, None) == 4
+
+
 def test_no_device_is_reported(lib):
     import torch
     if torch.cuda.is_available():

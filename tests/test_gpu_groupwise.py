@@ -7,7 +7,7 @@ mean sits on an fp32 rounding boundary, floating-point outputs within the normal
 import numpy as np
 import pytest
 
-from _util import make_case, nmax_err, packed_to_dev, packed_to_host, to_dev, to_host, tol_for
+from _util import decode_layout, make_case, nmax_err, packed_to_dev, packed_to_host, to_dev, to_host, tol_for
 from paper_2210_03858_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -277,3 +277,49 @@ def test_config2_block_grouped_sampled(bcq, oracle, kind, g):
     assert nmax_err(dx[tt, kk], oracle.bwd_input_at(a_ref, planes_gpu, dy, tt, kk)) <= tol
     rows = np.random.default_rng(7000 + g).choice(N, size=32, replace=False)
     assert nmax_err(da[:, rows], oracle.bwd_alpha_rows(planes_gpu, x, dy, rows, g=g)) <= tol
+
+
+DECODE_SHAPES = [
+    # T, N, K, g, q
+    (1, 16, 512, 512, 1),          # one tile, one segment
+    (8, 1000, 1056, 1056, 3),      # ragged rows (N % 16 != 0) and a last segment of 32 columns
+    (4, 2560, 2560, 2560, 4),      # a layer of workload 5
+    (16, 96, 4096, 4096, 8),       # two register halves, every plane
+    (31, 64, 1536, 512, 2),        # two token tiles, group-wise scales
+    (8, 14336, 4096, 4096, 4),     # many rows: activations shared through LDS, guard-free instantiation
+    (5, 14352, 4608, 1536, 3),     # many rows, ragged, group-wise, guarded instantiation
+    (12, 28672, 4096, 4096, 2),    # many rows, two register halves, one part
+]
+
+
+@pytest.mark.parametrize("T,N,K,g,q", DECODE_SHAPES)
+def test_decode_layout_and_forward(bcq, oracle, T, N, K, g, q):
+    """bcq_pack_decode is bit-exact against the layout definition; bcq_linear_fwd_decode meets the forward's bar."""
+    import torch
+    W, alpha, planes, packed, x, dy = make_case(3, "mlp_up", T, N, K, q, "bf16", oracle, g=g)
+    d_packed = packed_to_dev(packed)
+    tiled = bcq.bcq_pack_decode(d_packed)
+    _sync()
+    assert tiled.numel() * 4 == bcq.decode_layout_bytes(N, K, q)
+    assert np.array_equal(tiled.cpu().numpy().view(np.uint32), decode_layout(packed))
+    a3 = alpha if alpha.ndim == 3 else alpha[:, :, None]
+    y = bcq.bcq_linear_fwd_decode(tiled, to_dev(a3), to_dev(x, "bf16"), g=g, workspace=_ws(bcq, 1, T, N, K, g, q, 1))
+    y_canon = bcq.bcq_linear_fwd_grouped(d_packed, to_dev(a3), to_dev(x, "bf16"), g, workspace=_ws(bcq, 1, T, N, K, g, q, 1))
+    _sync()
+    assert nmax_err(to_host(y), oracle.fwd(alpha, planes, x)) <= tol_for("bf16")
+    if K % 128 == 0:  # same kernel, same order of sums (the canonical path of other K takes 4-byte plane loads)
+        assert torch.equal(y, y_canon)
+
+
+def test_decode_forward_rejects_what_it_does_not_take(bcq):
+    import torch
+    q, N, K = 2, 64, 1024
+    tiled = torch.zeros((bcq.decode_layout_bytes(N, K, q) // 4,), dtype=torch.int32, device="cuda")
+    alpha = torch.ones((q, N, 1), dtype=torch.float32, device="cuda")
+    ws = torch.empty((1 << 20,), dtype=torch.uint8, device="cuda")
+    for T, dt, g, w in ((32, torch.bfloat16, K, ws), (4, torch.float32, K, ws), (4, torch.bfloat16, 256, ws),
+                        (4, torch.bfloat16, K, None)):
+        x = torch.zeros((T, K), dtype=dt, device="cuda")
+        a = alpha if g == K else torch.ones((q, N, K // g), dtype=torch.float32, device="cuda")
+        with pytest.raises(bcq.BcqError):
+            bcq.bcq_linear_fwd_decode(tiled, a, x, g=g, workspace=w)
