@@ -177,6 +177,26 @@ def test_many_rows_streaming_parity(bcq, oracle, T, N, K, g, q):
     assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
 
 
+def test_many_rows_two_token_tiles_and_partial_training(bcq, oracle):
+    """17 .. 31 tokens are two token tiles of the forward (grid y); the scale gradient of the first planes only."""
+    T, N, K, q = 20, 28672, 4096, 2
+    W, alpha, planes, packed, x, dy = make_case(3, "mlp_up", T, N, K, q, "bf16", oracle)
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha[:, :, None])
+    y = bcq.bcq_linear_fwd_grouped(d_packed, d_alpha, to_dev(x, "bf16"), K, workspace=_ws(bcq, 1, T, N, K, K, q, 1))
+    tiled = bcq.bcq_pack_decode(d_packed)
+    y_dec = bcq.bcq_linear_fwd_decode(tiled, d_alpha, to_dev(x, "bf16"), workspace=_ws(bcq, 1, T, N, K, K, q, 1))
+    T2 = 7
+    da = bcq.bcq_linear_bwd_alpha_grouped(d_packed, to_dev(x[:T2], "bf16"), to_dev(dy[:T2], "bf16"), K, q_train=1,
+                                          grad_scale=0.5, workspace=_ws(bcq, 3, T2, N, K, K, q, 1))
+    _sync()
+    tol = tol_for("bf16")
+    ref = oracle.fwd(alpha, planes, x)
+    assert nmax_err(to_host(y), ref) <= tol
+    assert nmax_err(to_host(y_dec), ref) <= tol
+    ref_da = oracle.bwd_alpha(planes, x[:T2], dy[:T2], q_train=1, grad_scale=0.5)
+    assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
+
+
 def test_grouped_streaming_equals_rowwise_streaming_when_scales_repeat(bcq, oracle):
     """Group-wise scales that repeat one value per row must give the row-wise result of the same kernels
     (forward and input gradient); the scale gradient summed over the groups must equal the row-wise one."""
