@@ -28,6 +28,9 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy); see
 # profiles/bench_config2_hbm_traffic.md for the commands and the table.  Not measured live: null for other workloads.
 PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.76e7, (2, 4096, 4, "bwd_input"): 7.76e7}
+# the same for one whole step of `--config 5 --layer 16384x16384 --tokens 8` per layer copy (fwd 141.2 MB, dalpha 138.6 MB,
+# dx 154.5 MB, the three activation pre-kernels 2.8 MB; profiles/stream_large_layer_kernel_stats.md)
+PMC_TRAFFIC_STREAM_LAYER = {((16384, 16384), 8, 4): 4.370e8}
 
 
 def parse():
@@ -266,7 +269,8 @@ def main():
         achieved = bytes_step / (ms_per_step * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "stream_kernel + quant_act_kernel (fwd, dalpha, dx modes; whole captured step)",
                     "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 5), "traffic": None,
+                    "frac": round(achieved / PEAK_HBM_GBS, 5),
+                    "traffic": (PMC_TRAFFIC_STREAM_LAYER.get((custom, T, q), 0.0) * replicas or None) if not args.g else None,
                     "packed_plane_GBps": round(3 * sum(q * L["N"] * L["K"] / 8 for L in layers) / (ms_per_step * 1e-3) / 1e9, 1),
                     "algorithmic": "per op and layer: q*N*K/8 plane bytes + 4*q*N + activations; planes are read once "
                                    "by each of fwd, dx, dalpha"}
