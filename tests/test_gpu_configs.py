@@ -116,3 +116,67 @@ def test_config5_quantizer_all_kinds(bcq, oracle):
             N, K = synth.layer_shape(2560, kind)
             W = synth.weights(5, kind, N, K, extra=layer)
             _quantize_and_check(bcq, oracle, W, 4)
+
+
+@pytest.mark.parametrize("T", [4096, 8])
+def test_step_as_hip_graph_with_second_stream_matches_eager(bcq, oracle, T):
+    """The launch configuration bench.py times: one HIP graph of the step (fwd, dx on the capturing stream, the scale
+    gradients on a second stream of default priority, joined at the end).  Every replay must reproduce the eagerly
+    launched one-stream results bit for bit - with eager work and synchronisations between the replays - and those
+    results meet the oracle's bar on sampled outputs (one layer)."""
+    import torch
+    q, h = 4, 1024
+    layers = []
+    for kind in ("out", "mlp_up"):
+        N, K = synth.layer_shape(h, kind)
+        a_ref, planes_ref = oracle.quantize(synth.weights(2, kind, N, K), q)  # the oracle's planes: inputs of both sides
+        alpha, packed = to_dev(a_ref), packed_to_dev(oracle.pack(planes_ref))
+        L = dict(N=N, K=K, alpha=alpha, packed=packed, twin=bcq.bcq_pack_transposed(packed), a_ref=a_ref, planes_ref=planes_ref,
+                 x=torch.from_numpy(synth.activations(2, kind, T, K, 1, "bf16")).cuda().bfloat16(),
+                 dy=torch.from_numpy(synth.activations(2, kind, T, N, 2, "bf16")).cuda().bfloat16(),
+                 ws={op: torch.empty((max(bcq.workspace_bytes(op, T, N, K, q, 1), 16),), dtype=torch.uint8, device="cuda")
+                     for op in (1, 2, 3)})
+        for tag in ("e", "g"):  # eager / graph outputs
+            L["y" + tag] = torch.zeros((T, N), dtype=torch.bfloat16, device="cuda")
+            L["dx" + tag] = torch.zeros((T, K), dtype=torch.bfloat16, device="cuda")
+            L["da" + tag] = torch.zeros((q, N), dtype=torch.float32, device="cuda")
+        layers.append(L)
+
+    def fwd(L, t): bcq.bcq_linear_fwd(L["packed"], L["alpha"], L["x"], y=L["y" + t], workspace=L["ws"][1])
+    def dxf(L, t): bcq.bcq_linear_bwd_input(L["packed"], L["alpha"], L["dy"], packed_t=L["twin"], dx=L["dx" + t], workspace=L["ws"][2])
+    def daf(L, t): bcq.bcq_linear_bwd_alpha(L["packed"], L["x"], L["dy"], dalpha=L["da" + t], workspace=L["ws"][3])
+
+    for L in layers:  # eager, one stream (also the warm-up that sets the kernels' attributes before the capture)
+        fwd(L, "e"), dxf(L, "e"), daf(L, "e")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        main = torch.cuda.current_stream()
+        side.wait_stream(main)
+        for L in layers:
+            fwd(L, "g")
+            with torch.cuda.stream(side):
+                daf(L, "g")
+            dxf(L, "g")
+        main.wait_stream(side)
+    for rep in range(3):
+        for L in layers:
+            for name in ("yg", "dxg", "dag"):
+                L[name].fill_(float(rep + 1))        # eager work between the replays; also proves the replay rewrites all
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for L in layers:
+            assert torch.equal(L["yg"], L["ye"]), rep
+            assert torch.equal(L["dxg"], L["dxe"]), rep
+            assert torch.equal(L["dag"], L["dae"]), rep
+    # the eager results against the oracle, sampled (first layer)
+    L = layers[0]
+    N, K = L["N"], L["K"]
+    rng = np.random.default_rng(5)
+    x_h = synth.activations(2, "out", T, K, 1, "bf16")
+    ts, ns = rng.integers(0, T, 512), rng.integers(0, N, 512)
+    y_ref = oracle.fwd_at(L["a_ref"], L["planes_ref"], x_h, ts, ns)
+    scale = np.abs(y_ref).max()
+    assert np.abs(L["ye"].float().cpu().numpy()[ts, ns] - y_ref).max() / scale <= tol_for("bf16")
