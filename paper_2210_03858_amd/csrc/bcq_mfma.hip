@@ -234,9 +234,6 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     const int64_t kmax = R - 8;
     u32x4 areg[NA];
     auto load_a = [&](int64_t k0) {
-#ifdef BCQ_PROBE_NO_A
-        if (k0 > 0) return;
-#endif
         int64_t k = k0 + lc * 8;
         k = k < kmax ? k : kmax;
 #pragma unroll
@@ -259,9 +256,6 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     }
     u32x4 b[KS][TN];  // [kk][j]; slot kk is refilled for the next K-step right after its MFMAs are issued
     auto load_b = [&](int kk, int64_t step) {
-#ifdef BCQ_PROBE_NO_B
-        if (step > 0) return;
-#endif
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[kk][j] = bptr[j][(step * KS + kk) * 64];
     };
@@ -323,18 +317,6 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     // Pass the tile through LDS (64 tokens per wave at a time) so that global stores are 16 B per lane and
     // whole rows of 64 TN bytes are contiguous.
     constexpr int EROW = Cfg::EPI_ROWB;
-#ifdef BCQ_PROBE_NO_STORE
-    {
-        float keep = 0.f;
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) keep += acc[i][j][v];
-        if (keep != 123.456f) return;
-    }
-#endif
     const bool vec_ok = (ldc % 8 == 0);
     if (vec_ok) {
         unsigned char* ew = smem + wave * 64 * EROW;
@@ -642,18 +624,6 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
     }
     __syncthreads();
 
-#ifdef BCQ_PROBE_NO_EPI
-    {
-        float keep = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) keep += acc[i][j][v];
-        if (keep != 123.456f) return;
-    }
-#endif
     // epilogue: signed sums over this wave's 128 k for each plane; lane owns n = n_base + j*32 + lane%32.
     // All packed words of all trained planes are requested first (one memory latency instead of one per plane);
     // a sign is applied by XOR-ing the (inverted) plane bit into the fp32 sign bit: shift, bit-op, add per value.

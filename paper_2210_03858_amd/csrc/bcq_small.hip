@@ -179,15 +179,8 @@ __global__ __launch_bounds__(512) void small_kernel(const uint32_t* __restrict__
                         for (int r = 0; r < R; ++r)
 #pragma unroll
                             for (int i = 0; i < PPP; ++i) {
-#if defined(BCQ_PROBE_NO_MFMA)
-                                acc[r][i][0] += __builtin_bit_cast(float, bits[r][i][j]) + (float)v[0];
-#elif defined(BCQ_PROBE_NO_EXPAND)
-                                acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, v, acc[r][i], 0, 0, 0);
-                                acc[r][i][0] += __builtin_bit_cast(float, bits[r][i][j]);
-#else
                                 acc[r][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(expand_signs(bits[r][i][j], u), v,
                                                                                     acc[r][i], 0, 0, 0);
-#endif
                             }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -305,10 +298,6 @@ static SmallPlan small_plan(int64_t rows, int64_t cw) {
     }
     p.W = best_w;
     p.segs_per_wave = (int)((segs + best_w - 1) / best_w);
-#ifdef BCQ_PROBE_PLAN
-    if (getenv("BCQ_W")) { p.W = atoi(getenv("BCQ_W")); if (p.W > segs) p.W = (int)segs; p.segs_per_wave = (int)((segs + p.W - 1) / p.W); }
-    if (getenv("BCQ_R")) p.R = atoi(getenv("BCQ_R"));
-#endif
     p.grid_x = (unsigned)((rows + 16 * p.R - 1) / (16 * p.R));
     return p;
 }

@@ -915,10 +915,6 @@ static StreamPlan stream_plan(int64_t T, int64_t rows, int64_t cw, int gsegs = 0
         p.W = (int)((groups + gpw - 1) / gpw);
         p.segs_per_wave = (int)(gpw * gsegs);
     }
-#ifdef BCQ_PROBE_PLAN
-    if (getenv("BCQ_R")) p.R = atoi(getenv("BCQ_R"));
-    if (getenv("BCQ_W")) { p.W = atoi(getenv("BCQ_W")); if (p.W > p.segs) p.W = (int)p.segs; p.segs_per_wave = (int)((p.segs + p.W - 1) / p.W); }
-#endif
     p.grid_x = (unsigned)((rows + 16 * p.R - 1) / (16 * p.R));
     p.xq_bytes = (size_t)p.tiles * p.segs * 4 * p.halves * QBLK;
     p.sq_bytes = (size_t)p.tiles * p.segs * p.halves * QSCL;
@@ -946,10 +942,6 @@ static LdsPlan lds_plan(int64_t rows, int64_t segs, int halves, int gsegs, int q
         kw = 1;
     else if (halves == 1 && (rt + 3) / 4 >= 224)
         kw = 2;
-#ifdef BCQ_PROBE_PLAN
-    if (getenv("BCQ_LDS")) kw = atoi(getenv("BCQ_LDS"));
-    if (kw == 2 && halves != 1) kw = 0;
-#endif
     if (kw == 0 || segs < 2 * LCS * kw) return p;
     int64_t spp = (segs + kw - 1) / kw;
     if (gsegs > 0) spp = (spp + gsegs - 1) / gsegs * gsegs;  // whole scale groups per part
