@@ -195,7 +195,8 @@ def main():
 
     # ---------------- warm-up: every op bracketed by events -> per-op table and the dominant op family
     warm_events = []
-    for _ in range(max(args.warmup, 1)):
+    n_warm = max(args.warmup, 2)  # at least two: the per-op figures skip the first step (one-time set-up of the kernels)
+    for _ in range(n_warm):
         step(warm_events)
     torch.cuda.synchronize()
     graph = None
@@ -242,7 +243,7 @@ def main():
         # the eagerly launched one-stream warm-up steps of this run (all but the first, which pays one-time set-up)
         events = [e for e in warm_events[len(ops) * len(layers):] if e[0] == dom] or None
         roofline_note = ("per-launch figures from the %d eagerly launched one-stream warm-up steps of this run; the timed "
-                         "region %s" % (max(args.warmup, 1) - 1,
+                         "region %s" % (n_warm - 1,
                                         " and ".join(([("replays a HIP graph of the same step")] if graph is not None else [])
                                                      + (["runs dalpha on a second stream"] if side is not None else []))))
     if events:
