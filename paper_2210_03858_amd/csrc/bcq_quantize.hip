@@ -31,6 +31,37 @@ __device__ __forceinline__ void write_lane(uint32_t& dst, uint32_t v) {
     asm volatile("s_nop 4\n\tv_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(v), "n"(L));
 }
 
+// The same for four chunks at once: four sign-bit compares (sign bit clear <=> high word > -1 as an integer), then
+// the eight lane writes.  Written out so that every lane write comes at least four issue slots after the compare
+// whose scalar result it reads - the compares of the other chunks and one s_nop fill them - instead of five idle
+// slots before each of the eight.  Both blocks are volatile, so nothing moves between or across them in a way that
+// shortens those distances.
+template <int L0>
+__device__ __forceinline__ void ballots4(int h0, int h1, int h2, int h3, uint32_t& lo, uint32_t& hi) {
+    uint64_t m0, m1, m2, m3;
+    asm volatile(
+        "v_cmp_gt_i32 %0, %4, -1\n\t"
+        "v_cmp_gt_i32 %1, %5, -1\n\t"
+        "v_cmp_gt_i32 %2, %6, -1\n\t"
+        "v_cmp_gt_i32 %3, %7, -1"
+        : "=s"(m0), "=s"(m1), "=s"(m2), "=s"(m3)
+        : "v"(h0), "v"(h1), "v"(h2), "v"(h3));
+    asm volatile(
+        "s_nop 0\n\t"
+        "v_writelane_b32 %0, %2, %10\n\t"
+        "v_writelane_b32 %1, %3, %10\n\t"
+        "v_writelane_b32 %0, %4, %11\n\t"
+        "v_writelane_b32 %1, %5, %11\n\t"
+        "v_writelane_b32 %0, %6, %12\n\t"
+        "v_writelane_b32 %1, %7, %12\n\t"
+        "v_writelane_b32 %0, %8, %13\n\t"
+        "v_writelane_b32 %1, %9, %13"
+        : "+v"(lo), "+v"(hi)
+        : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)),
+          "s"((uint32_t)m2), "s"((uint32_t)(m2 >> 32)), "s"((uint32_t)m3), "s"((uint32_t)(m3 >> 32)),
+          "n"(L0), "n"(L0 + 1), "n"(L0 + 2), "n"(L0 + 3));
+}
+
 // Chunk cc of a row = columns 64 cc .. 64 cc + 63.  WAVE_ROW = true: wave w owns the whole row 4 blockIdx.x + w,
 // register r[c] of lane l holds column 64 c + l.  WAVE_ROW = false: the four waves of the block share row
 // blockIdx.x, wave w takes chunks 4 c + w.  Either way every chunk of a wave is entirely inside the row except
@@ -73,15 +104,26 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
     for (int i = 0; i < q; ++i) {
         double s = 0.0;
         uint32_t mine_lo = 0u, mine_hi = 0u;
-        static_for<0, CMAX>([&](auto cc) {
-            constexpr int c = decltype(cc)::value;
-            if (EXACT || c < nch) {
-                s += fabs(r[c]);
-                const uint64_t m = __ballot((int)__double2hiint(r[c]) >= 0);  // sign bit clear <=> +1
-                write_lane<c>(mine_lo, (uint32_t)m);                          // the ballot is wave-uniform
-                write_lane<c>(mine_hi, (uint32_t)(m >> 32));
-            }
-        });
+        if constexpr (CMAX % 4 == 0) {
+            // chunks beyond the row hold +0.0: they add nothing to the sum, and their ballots land in lanes that
+            // store nothing, so no guard is needed here
+            static_for<0, CMAX / 4>([&](auto gg) {
+                constexpr int c = 4 * decltype(gg)::value;
+                s += (fabs(r[c]) + fabs(r[c + 1])) + (fabs(r[c + 2]) + fabs(r[c + 3]));
+                ballots4<c>(__double2hiint(r[c]), __double2hiint(r[c + 1]), __double2hiint(r[c + 2]),
+                            __double2hiint(r[c + 3]), mine_lo, mine_hi);
+            });
+        } else {
+            static_for<0, CMAX>([&](auto cc) {
+                constexpr int c = decltype(cc)::value;
+                if (EXACT || c < nch) {
+                    s += fabs(r[c]);
+                    const uint64_t m = __ballot((int)__double2hiint(r[c]) >= 0);  // sign bit clear <=> +1
+                    write_lane<c>(mine_lo, (uint32_t)m);                          // the ballot is wave-uniform
+                    write_lane<c>(mine_hi, (uint32_t)(m >> 32));
+                }
+            });
+        }
         // sum of |r| over the row in fp64
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
