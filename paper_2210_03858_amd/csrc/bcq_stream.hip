@@ -60,44 +60,11 @@ __device__ __forceinline__ uint32_t q_pack_bf16x2(float lo, float hi) {
 // 16 seg + 4 G + j of the contraction axis (32 columns), finds the block's power-of-two scale, and writes
 // 2 x 16 bytes per term plus the scale bytes.  DX: the activation is dy[t][n] * alpha_i[n][grp] for set
 // blockIdx.y = i NG + grp (NG scale groups along the columns of W; row-wise scales: NG = 1).
-template <int MODE>
-__global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict__ act, const float* __restrict__ alpha,
-                                                        int64_t T, int64_t C, int64_t segs, int halves, int tiles,
-                                                        unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
-                                                        size_t xq_plane, size_t sq_plane, int NG) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
-    const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
-    if (tile >= tiles) return;
-    const int plane = blockIdx.y;
-    xq += (size_t)plane * xq_plane;
-    sq += (size_t)plane * sq_plane;
-    const int64_t t = tile * 16 + tl;
-    const bool one_half = (halves == 1);
-    const int64_t word = seg * 16 + 4 * G + j;  // 32 columns of the contraction axis
-    const bool live = (t < T) && (word * 32 < C) && (!one_half || tl < 8);
-    float v[32];
-    if (live) {
-        const q_u32x4* src = reinterpret_cast<const q_u32x4*>(act + t * C + word * 32);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const q_u32x4 r = src[b];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[8 * b + 2 * e] = __uint_as_float(r[e] << 16);
-                v[8 * b + 2 * e + 1] = __uint_as_float(r[e] & 0xFFFF0000u);
-            }
-        }
-        if (MODE == STREAM_DX) {
-            const int pl_i = plane / NG, grp = plane % NG;
-            const float* a = alpha + ((int64_t)pl_i * C + word * 32) * NG + grp;  // alpha[i][n][grp], n = 32 word + e
-#pragma unroll
-            for (int e = 0; e < 32; ++e) v[e] *= a[(int64_t)e * NG];
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < 32; ++e) v[e] = 0.f;
-    }
+// One unit of the re-coding: the 32 values v of one token (column tl of its 16-token tile) and one packed-word
+// position (block G of instruction j) -> two FP8 terms and their scale bytes, stored into the operand blocks of
+// instruction j (xb: [half][2 KiB]) and the scales of the segment (sb: [half][256 B]); global memory or LDS.
+__device__ __forceinline__ void recode_unit(const float (&v)[32], int tl, int G, int j, bool one_half, unsigned char* xb,
+                                            unsigned char* sb) {
     float amax = 0.f;
 #pragma unroll
     for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
@@ -131,22 +98,68 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
         }
     }
     // chunk 2 G + cc (cc = 0, 1) lives in lane group (2 G + cc) % 4, register half (2 G + cc) / 4; an operand block is
-    // stored as [register half][lane][16 B], so that a 16-byte read per lane is contiguous over the wave
+    // stored as [register half][lane][16 B], so that a 16-byte read per lane is contiguous over the wave.
+    // One half (at most 8 tokens): the second term of token tl sits in column tl + 8 of the same block.
     const int col1 = tl, col2 = one_half ? tl + 8 : tl;
     const int half2 = one_half ? 0 : 1;
-    if (one_half && tl >= 8) return;  // columns 8 .. 15 of the single half belong to the second term of tokens 0 .. 7
-    const size_t blk = ((size_t)(tile * segs + seg) * 4 + j) * halves;
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
         const int c = 2 * G + cc, gB = c & 3, hh = c >> 2;
         const q_u32x4 o1 = {t1[4 * cc], t1[4 * cc + 1], t1[4 * cc + 2], t1[4 * cc + 3]};
         const q_u32x4 o2 = {t2[4 * cc], t2[4 * cc + 1], t2[4 * cc + 2], t2[4 * cc + 3]};
-        *reinterpret_cast<q_u32x4*>(xq + (blk + 0) * QBLK + hh * (QBLK / 2) + (gB * 16 + col1) * 16) = o1;
-        *reinterpret_cast<q_u32x4*>(xq + (blk + half2) * QBLK + hh * (QBLK / 2) + (gB * 16 + col2) * 16) = o2;
+        *reinterpret_cast<q_u32x4*>(xb + hh * (QBLK / 2) + (gB * 16 + col1) * 16) = o1;
+        *reinterpret_cast<q_u32x4*>(xb + half2 * QBLK + hh * (QBLK / 2) + (gB * 16 + col2) * 16) = o2;
     }
-    const size_t sblk = (size_t)(tile * segs + seg) * halves;
-    sq[(sblk + 0) * QSCL + (col1 + 16 * G) * 4 + j] = (unsigned char)sb1;
-    sq[(sblk + half2) * QSCL + (col2 + 16 * G) * 4 + j] = (unsigned char)sb2;
+    sb[(col1 + 16 * G) * 4 + j] = (unsigned char)sb1;
+    sb[half2 * QSCL + (col2 + 16 * G) * 4 + j] = (unsigned char)sb2;
+}
+
+// 32 bf16 values -> fp32
+__device__ __forceinline__ void load_unit(const bf16_t* src, float (&v)[32]) {
+    const q_u32x4* s4 = reinterpret_cast<const q_u32x4*>(src);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const q_u32x4 r = s4[b];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[8 * b + 2 * e] = __uint_as_float(r[e] << 16);
+            v[8 * b + 2 * e + 1] = __uint_as_float(r[e] & 0xFFFF0000u);
+        }
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict__ act, const float* __restrict__ alpha,
+                                                        int64_t T, int64_t C, int64_t segs, int halves, int tiles,
+                                                        unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
+                                                        size_t xq_plane, size_t sq_plane, int NG) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
+    const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
+    if (tile >= tiles) return;
+    const int plane = blockIdx.y;
+    xq += (size_t)plane * xq_plane;
+    sq += (size_t)plane * sq_plane;
+    const int64_t t = tile * 16 + tl;
+    const bool one_half = (halves == 1);
+    if (one_half && tl >= 8) return;  // columns 8 .. 15 of the single half belong to the second term of tokens 0 .. 7
+    const int64_t word = seg * 16 + 4 * G + j;  // 32 columns of the contraction axis
+    const bool live = (t < T) && (word * 32 < C);
+    float v[32];
+    if (live) {
+        load_unit(act + t * C + word * 32, v);
+        if (MODE == STREAM_DX) {
+            const int pl_i = plane / NG, grp = plane % NG;
+            const float* a = alpha + ((int64_t)pl_i * C + word * 32) * NG + grp;  // alpha[i][n][grp], n = 32 word + e
+#pragma unroll
+            for (int e = 0; e < 32; ++e) v[e] *= a[(int64_t)e * NG];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 32; ++e) v[e] = 0.f;
+    }
+    recode_unit(v, tl, G, j, one_half, xq + ((size_t)(tile * segs + seg) * 4 + j) * halves * QBLK,
+                sq + (size_t)(tile * segs + seg) * halves * QSCL);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -513,6 +526,89 @@ __global__ __launch_bounds__(512) void stream_kernel(const uint32_t* __restrict_
     }
 }
 
+// Common end of the one-row-tile kernels.  acc: plane sums (or y in slot 0 with ep = 1, 0, ..) of this wave's part of
+// the contraction; ep: FWD alpha_i of the lane's 4 rows, DALPHA dy of the lane's token (slot 0).  The nparts parts of a
+// row tile are added in part order through `red` (slot of part p of row tile `sub`: p * pstride + sub); every wave
+// of the workgroup must call this (it contains a barrier), and `red` must be free for reuse when it does.
+template <int MODE, int QP, bool TWO>
+__device__ __forceinline__ void stream_finish(q_f32x4 (&acc)[QP], float (&ep)[QP][4], float* red, int nparts, int part_id,
+                                              int pstride, int sub, int lane, int64_t row0, int64_t rows, int64_t tok,
+                                              bool tok_live, int q_used, float scale, void* out) {
+    const int rl = lane & 15, g = lane >> 4;
+    if (!TWO) {  // one half: add the second term's columns (t + 8) onto the first term's (t)
+#pragma unroll
+        for (int i = 0; i < QP; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][v] += __shfl_xor(acc[i][v], 8);
+    }
+    constexpr int NOUT = (MODE == STREAM_DALPHA) ? QP : 1;
+    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
+    q_f32x4 part[NOUT];
+    if (MODE == STREAM_FWD) {
+        q_f32x4 y = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < QP; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) y[v] += ep[i][v] * acc[i][v];  // alpha of unused planes is 0
+        part[0] = y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < NOUT; ++i) part[i] = acc[i];
+    }
+    if (nparts > 1) {
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout && part_id > 0)
+                *reinterpret_cast<q_f32x4*>(&red[(((part_id * pstride + sub) * nout + o) * 64 + lane) * 4]) = part[o];
+        __syncthreads();
+        if (part_id != 0) return;
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout) {
+                q_f32x4 sum = part[o];
+                for (int w = 1; w < nparts; ++w)
+                    sum += *reinterpret_cast<const q_f32x4*>(&red[(((w * pstride + sub) * nout + o) * 64 + lane) * 4]);
+                part[o] = sum;
+            }
+    }
+    const bool col_live = tok_live && (TWO || rl < 8);  // with one half, columns 8 .. 15 duplicate columns 0 .. 7
+    const int64_t n = row0 + 4 * g;                     // first of this lane's 4 rows
+    if (MODE == STREAM_DALPHA) {
+#pragma unroll
+        for (int o = 0; o < NOUT; ++o)
+            if (o < nout) {
+                q_f32x4 sum;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float x = col_live ? ep[0][v] * part[o][v] : 0.f;
+                    x += __shfl_xor(x, 1);
+                    x += __shfl_xor(x, 2);
+                    x += __shfl_xor(x, 4);
+                    x += __shfl_xor(x, 8);
+                    sum[v] = x * scale;
+                }
+                if (rl == 0)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (n + v < rows) reinterpret_cast<float*>(out)[(int64_t)o * rows + n + v] = sum[v];
+            }
+    } else {
+        bf16_t* o = reinterpret_cast<bf16_t*>(out);
+        if (col_live) {
+            if (n + 3 < rows && (rows & 3) == 0) {
+                q_u32x2 pk;
+                pk[0] = q_pack_bf16x2(part[0][0], part[0][1]);
+                pk[1] = q_pack_bf16x2(part[0][2], part[0][3]);
+                *reinterpret_cast<q_u32x2*>(o + tok * rows + n) = pk;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (n + v < rows) o[tok * rows + n + v] = f32_to_bf16(part[0][v]);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Forward / scale gradient for plane matrices with many rows: the activation operand goes through LDS.
 // A compute unit keeps a limited number of cache misses in flight, and in stream_kernel most of them fetch the
@@ -802,78 +898,208 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
             for (int v = 0; v < 4; ++v) ep[i][v] = 0.f;
         }
     }
-    if (!TWO) {  // one half: add the second term's columns (t + 8) onto the first term's (t)
+    stream_finish<MODE, QP, TWO>(acc, ep, reinterpret_cast<float*>(lds), KW, kp, RW, rtile, lane, row0, rows, tok, tok_live,
+                                 q_used, scale, out);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Forward / scale gradient when a wave has only one or two segments (small layers: the call is bound by launch and
+// memory latency, not by bandwidth): the wave re-codes the activations of its own segment into LDS itself, so the
+// call is ONE kernel and needs no workspace.  The re-coding costs about 480 vector-ALU operations per lane and
+// segment (it is repeated by every row tile), which is why larger layers keep the separate pre-kernel.
+// One workgroup = one row tile; its W waves split the segments.  LDS: W wave-private staging areas
+// ([4 instructions][halves][2 KiB] + [halves][256 B] scales), reused for the cross-wave sum at the end.
+// gsegs == 0: row-wise scales; else groups of gsegs segments (every wave owns whole groups).
+template <int MODE, int QP, bool TWO>
+__global__ __launch_bounds__(512) void stream_fused_kernel(const uint32_t* __restrict__ planes,
+                                                            const bf16_t* __restrict__ act,
+                                                            const float* __restrict__ alpha,
+                                                            const bf16_t* __restrict__ dy, void* __restrict__ out,
+                                                            int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
+                                                            int segs_per_wave, int64_t segs, int gsegs, int G) {
+    static_assert(MODE != STREAM_DX, "forward and scale gradient only");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int H = TWO ? 2 : 1;
+    constexpr int WST = 4 * H * QBLK + H * QSCL;  // staging bytes of one wave
+    constexpr int NU = 2 * H;                     // re-coding units per lane and segment (128 H live units)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int rl = lane & 15, g = lane >> 4;
+    const int64_t row0 = (int64_t)blockIdx.x * 16;
+    const int64_t t0 = (int64_t)blockIdx.y * 16;
+    const int64_t C = cw * 32;
+    const bool grouped = gsegs > 0;
+    unsigned char* wst = lds + wave * WST;
+
+    q_f32x4 acc[QP];
 #pragma unroll
-        for (int i = 0; i < QP; ++i)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[i][v] += __shfl_xor(acc[i][v], 8);
+    for (int i = 0; i < QP; ++i) acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint32_t cw32 = (uint32_t)cw;
+    uint32_t roff;
+    {
+        int64_t rr = row0 + rl;
+        rr = rr < rows ? rr : rows - 1;  // rows beyond the matrix give outputs that are never stored
+        roff = (uint32_t)(rr * cw);
     }
-    constexpr int NOUT = (MODE == STREAM_DALPHA) ? QP : 1;
-    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
-    q_f32x4 part[NOUT];
-    if (MODE == STREAM_FWD) {
-        q_f32x4 y = {0.f, 0.f, 0.f, 0.f};
+    const int64_t plane_stride = rows * cw;
+    const int tcol = TWO ? rl : (rl & 7);
+    const bool tok_live = (t0 + tcol) < T;
+    const int64_t tok = tok_live ? t0 + tcol : T - 1;
+    float ep[QP][4];
 #pragma unroll
-        for (int i = 0; i < QP; ++i)
+    for (int v = 0; v < 4; ++v) {
+        int64_t n = row0 + 4 * g + v;
+        const bool n_live = n < rows;
+        n = n_live ? n : rows - 1;
+        if (MODE == STREAM_FWD) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) y[v] += ep[i][v] * acc[i][v];  // alpha of unused planes is 0
-        part[0] = y;
-    } else {
-#pragma unroll
-        for (int i = 0; i < NOUT; ++i) part[i] = acc[i];
-    }
-    if (KW > 1) {  // sum over the parts in part order (the staging buffers are free after the last barrier)
-        float* red = reinterpret_cast<float*>(lds);
-#pragma unroll
-        for (int o = 0; o < NOUT; ++o)
-            if (o < nout && kp > 0) *reinterpret_cast<q_f32x4*>(&red[(((kp * RW + rtile) * nout + o) * 64 + lane) * 4]) = part[o];
-        __syncthreads();
-        if (kp != 0) return;
-#pragma unroll
-        for (int o = 0; o < NOUT; ++o)
-            if (o < nout) {
-                q_f32x4 sum = part[o];
-                for (int w = 1; w < KW; ++w)
-                    sum += *reinterpret_cast<const q_f32x4*>(&red[(((w * RW + rtile) * nout + o) * 64 + lane) * 4]);
-                part[o] = sum;
-            }
-    }
-    const bool col_live = tok_live && (TWO || rl < 8);  // with one half, columns 8 .. 15 duplicate columns 0 .. 7
-    const int64_t n = row0 + 4 * g;                     // first of this lane's 4 rows
-    if (MODE == STREAM_DALPHA) {
-#pragma unroll
-        for (int o = 0; o < NOUT; ++o)
-            if (o < nout) {
-                q_f32x4 sum;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float x = col_live ? ep[0][v] * part[o][v] : 0.f;
-                    x += __shfl_xor(x, 1);
-                    x += __shfl_xor(x, 2);
-                    x += __shfl_xor(x, 4);
-                    x += __shfl_xor(x, 8);
-                    sum[v] = x * scale;
-                }
-                if (rl == 0)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (n + v < rows) reinterpret_cast<float*>(out)[(int64_t)o * rows + n + v] = sum[v];
-            }
-    } else {
-        bf16_t* o = reinterpret_cast<bf16_t*>(out);
-        if (col_live) {
-            if (n + 3 < rows && (rows & 3) == 0) {
-                q_u32x2 pk;
-                pk[0] = q_pack_bf16x2(part[0][0], part[0][1]);
-                pk[1] = q_pack_bf16x2(part[0][2], part[0][3]);
-                *reinterpret_cast<q_u32x2*>(o + tok * rows + n) = pk;
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (n + v < rows) o[tok * rows + n + v] = f32_to_bf16(part[0][v]);
-            }
+            for (int i = 0; i < QP; ++i) ep[i][v] = (!grouped && i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+        } else {
+            ep[0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
         }
     }
+    q_f32x4 yv = {0.f, 0.f, 0.f, 0.f};
+    float ga[QP][4];  // group-wise forward: scales of the current group
+
+    const int seg_begin = wave * segs_per_wave;
+    int seg_end = seg_begin + segs_per_wave;
+    seg_end = seg_end < (int)segs ? seg_end : (int)segs;
+    for (int seg = seg_begin; seg < seg_end; ++seg) {
+        // activations of this segment first (loads return in issue order and these are needed first), then the planes
+        q_u32x4 raw[NU][4];
+        bool live[NU];
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int uu = lane + 64 * u;
+            const int Gb = uu & 3, tl = (uu >> 2) & (8 * H - 1), j = uu >> (TWO ? 6 : 5);
+            const int64_t t = t0 + tl, word = (int64_t)seg * 16 + 4 * Gb + j;
+            live[u] = (t < T) && (word * 32 < C);
+            const q_u32x4* src = reinterpret_cast<const q_u32x4*>(act + (live[u] ? t * C + word * 32 : 0));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) raw[u][b] = src[b];  // a dead unit reads the first 64 bytes of act (in bounds)
+        }
+        uint32_t bits[QP][4];
+        {
+            uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
+#pragma unroll
+            for (int i = 0; i < QP; ++i) {
+                const uint32_t* pl = planes + (int64_t)(i < q_used ? i : q_used - 1) * plane_stride;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    uint32_t wj = w0 + (uint32_t)jj;
+                    wj = wj < cw32 ? wj : cw32 - 1u;  // columns beyond C meet zero activations
+                    bits[i][jj] = pl[roff + wj];
+                }
+            }
+        }
+        if (grouped && MODE == STREAM_FWD && (seg == seg_begin || seg % gsegs == 0)) {
+            const int grp = seg / gsegs;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                int64_t n = row0 + 4 * g + v;
+                n = n < rows ? n : rows - 1;
+#pragma unroll
+                for (int i = 0; i < QP; ++i) ga[i][v] = (i < q_used) ? alpha[((int64_t)i * rows + n) * G + grp] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int uu = lane + 64 * u;
+            const int Gb = uu & 3, tl = (uu >> 2) & (8 * H - 1), j = uu >> (TWO ? 6 : 5);
+            float v[32];
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[8 * b + 2 * e] = live[u] ? __uint_as_float(raw[u][b][e] << 16) : 0.f;
+                    v[8 * b + 2 * e + 1] = live[u] ? __uint_as_float(raw[u][b][e] & 0xFFFF0000u) : 0.f;
+                }
+            recode_unit(v, tl, Gb, j, !TWO, wst + j * H * QBLK, wst + 4 * H * QBLK);
+        }
+        // the staging area is private to the wave: LDS operations of one wave complete in issue order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        int sv[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) sv[h] = *reinterpret_cast<const int*>(wst + 4 * H * QBLK + h * QSCL + lane * 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            q_i32x8 bo[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const unsigned char* bp = wst + (j * H + h) * QBLK + lane * 16;
+                const q_u32x4 lo = *reinterpret_cast<const q_u32x4*>(bp);
+                const q_u32x4 hi = *reinterpret_cast<const q_u32x4*>(bp + QBLK / 2);
+                bo[h] = q_i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            }
+#pragma unroll
+            for (int i = 0; i < QP; ++i) {
+                q_i32x8 aop;
+                expand_one(bits[i][j], aop);
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    // the instruction picks byte j of the scale register (its op_sel): j must be a constant
+                    if (j == 0)
+                        acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 0, sv[h]);
+                    else if (j == 1)
+                        acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 1, sv[h]);
+                    else if (j == 2)
+                        acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 2, sv[h]);
+                    else
+                        acc[i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aop, bo[h], acc[i], 4, 0, 0, 127, 3, sv[h]);
+                }
+            }
+        }
+        if (grouped && ((seg + 1) % gsegs == 0 || seg + 1 == seg_end)) {  // uniform: a scale group ends
+            const int grp = seg / gsegs;
+            if (MODE == STREAM_FWD) {
+#pragma unroll
+                for (int i = 0; i < QP; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) yv[v] += ga[i][v] * acc[i][v];
+            } else {
+                const int64_t n = row0 + 4 * g;
+#pragma unroll
+                for (int o = 0; o < QP; ++o)
+                    if (o < q_used) {
+                        q_f32x4 sum;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            float x = ep[0][v] * acc[o][v];
+                            x += __shfl_xor(x, 1);
+                            x += __shfl_xor(x, 2);
+                            x += __shfl_xor(x, 4);
+                            x += __shfl_xor(x, 8);
+                            sum[v] = x * scale;
+                        }
+                        if (rl == 0)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                if (n + v < rows) reinterpret_cast<float*>(out)[(((int64_t)o * rows + n + v) * G) + grp] = sum[v];
+                    }
+            }
+#pragma unroll
+            for (int i = 0; i < QP; ++i) acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        // the next segment overwrites the staging area: its reads above are done (same wave, issue order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (grouped && MODE == STREAM_DALPHA) return;  // every group was stored at its end
+    if (grouped && MODE == STREAM_FWD) {            // continue with y in place of the plane sums
+        acc[0] = yv;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ep[0][v] = 1.f;
+#pragma unroll
+        for (int i = 1; i < QP; ++i) {
+            acc[i] = q_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ep[i][v] = 0.f;
+        }
+    }
+    if (W > 1) __syncthreads();  // the cross-wave sum reuses the staging areas
+    stream_finish<MODE, QP, TWO>(acc, ep, reinterpret_cast<float*>(lds), W, wave, 1, 0, lane, row0, rows, tok, tok_live,
+                                 q_used, scale, out);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1013,6 +1239,50 @@ static hipError_t launch_lds(const uint32_t* planes, const unsigned char* xq, co
 }
 
 // g = group size of the scales along the columns of W (K of the layer); g == layer K means row-wise.
+// The single-kernel form is used when a wave has one segment and all waves of the launch are resident at once
+// (every wave repeats the re-coding of its segment, about 2.5 us of vector-ALU work; measured: 2560 x 2560 and
+// 5120 x 1280 gain 2.3 - 2.7 us per call, 7680 x 2560 loses 1.7 us, 10240 x 2560 loses 8 us)
+constexpr int FUSED_MAX_SEGS = 1;
+constexpr int64_t FUSED_MAX_WAVES = 1024;
+
+template <int MODE, int QP, bool TWO>
+static hipError_t launch_fused_cfg(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy,
+                                   void* out, int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
+                                   const StreamPlan& p, int gsegs, int G, hipStream_t st) {
+    constexpr int H = TWO ? 2 : 1;
+    const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
+    const size_t stage = (size_t)p.W * (4 * H * QBLK + H * QSCL), red = (size_t)p.W * nout * 1024;
+    const size_t lds = stage > red ? stage : red;
+    static size_t lds_allowed = 64 * 1024;
+    if (lds > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute((const void*)stream_fused_kernel<MODE, QP, TWO>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_allowed = lds;
+    }
+    hipLaunchKernelGGL((stream_fused_kernel<MODE, QP, TWO>), dim3(p.grid_x, (unsigned)p.tiles), dim3((unsigned)(64 * p.W)),
+                       lds, st, planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, gsegs, G);
+    return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_fused(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
+                               int64_t T, int64_t rows, int64_t cw, int q_used, float scale, const StreamPlan& p,
+                               int gsegs, int G, hipStream_t st) {
+#define BCQ_FUSED_Q(QQ)                                                                                                \
+    if (p.halves == 2)                                                                                                 \
+        return launch_fused_cfg<MODE, QQ, true>(planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p, gsegs, G, st); \
+    return launch_fused_cfg<MODE, QQ, false>(planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p, gsegs, G, st);
+    switch (q_used <= 4 ? q_used : 8) {
+        case 1: BCQ_FUSED_Q(1)
+        case 2: BCQ_FUSED_Q(2)
+        case 3: BCQ_FUSED_Q(3)
+        case 4: BCQ_FUSED_Q(4)
+        default: BCQ_FUSED_Q(8)
+    }
+#undef BCQ_FUSED_Q
+}
+
 template <int MODE, bool TILED = false>
 static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const float* alpha, const bf16_t* dy, void* out,
                                 int64_t T, int64_t rows, int64_t cw, int q, int q_used, float scale, void* workspace,
@@ -1022,6 +1292,11 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     const int gsegs = (grouped && MODE != STREAM_DX) ? (int)(g / 512) : 0;  // needs g % 512 == 0 (checked by the caller)
     const StreamPlan p = stream_plan(T, rows, cw, gsegs);
     if (p.W < 1 || p.W > 8 || p.R != 1) return hipErrorInvalidConfiguration;  // compiled for at most 512 threads, R = 1
+    if constexpr (MODE != STREAM_DX && !TILED) {
+        int fused_max = FUSED_MAX_SEGS;
+        if (p.segs_per_wave <= fused_max && p.R == 1 && (int64_t)p.grid_x * p.tiles * p.W <= FUSED_MAX_WAVES)
+            return launch_fused<MODE>(planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p, gsegs, G, st);
+    }
     const int sets = (MODE == STREAM_DX) ? q * G : 1;
     unsigned char* xq = reinterpret_cast<unsigned char*>(workspace);
     unsigned char* sq = xq + (size_t)sets * p.xq_bytes;
