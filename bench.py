@@ -268,7 +268,7 @@ def main():
             planes_b = q * L["N"] * L["K"] / 8
             bytes_step += 3 * planes_b + 2 * 4 * q * L["N"] + 2 * sz * T * (L["K"] + L["N"]) + sz * T * (L["K"] + L["N"])
         achieved = bytes_step / (ms_per_step * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "stream_kernel + quant_act_kernel (fwd, dalpha, dx modes; whole captured step)",
+        roofline = {"bound": "hbm", "kernel": "stream_kernel / stream_lds_kernel / stream_fused_kernel + quant_act_kernel (fwd, dalpha, dx; whole captured step)",
                     "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(achieved / PEAK_HBM_GBS, 5),
                     "traffic": (PMC_TRAFFIC_STREAM_LAYER.get((custom, T, q), 0.0) * replicas or None) if not args.g else None,
