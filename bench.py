@@ -224,6 +224,20 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # spread of single steps (not part of `value`): up to 50 more steps, each bracketed by HIP events
+    spread = []
+    for _ in range(min(args.steps, 50)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        if graph is not None:
+            graph.replay()
+        else:
+            step()
+        b.record()
+        spread.append((a, b))
+    torch.cuda.synchronize()
+    spread = sorted(a.elapsed_time(b) for a, b in spread)
+
     flops_layer = {L["kind"]: 2.0 * T * L["N"] * L["K"] for L in layers}
     flops_step = 3.0 * sum(flops_layer.values())
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -340,6 +354,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(spread[len(spread) // 2], 4),
+        "ms_per_step_min": round(spread[0], 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
