@@ -206,9 +206,16 @@ def main():
             step()
         graph.replay()
         torch.cuda.synchronize()
-    fam_ms = {}
-    for op, kind, a, b in warm_events[-len(ops) * len(layers):]:
-        fam_ms[op] = fam_ms.get(op, 0.0) + a.elapsed_time(b)
+    # per op family: time per step, median over the warm-up steps but the first (which pays one-time set-up)
+    n_ev = len(ops) * len(layers)
+    fam_steps = {op: [] for op in ops}
+    for i in range(1, n_warm):
+        sums = dict.fromkeys(ops, 0.0)
+        for op, kind, a, b in warm_events[i * n_ev:(i + 1) * n_ev]:
+            sums[op] += a.elapsed_time(b)
+        for op in ops:
+            fam_steps[op].append(sums[op])
+    fam_ms = {op: sorted(v)[(len(v) - 1) // 2] for op, v in fam_steps.items()}  # lower median
     dom = max(fam_ms, key=lambda k: fam_ms[k])
 
     # ---------------- timed region: exactly --steps steps; events only around the dominant family's launches
@@ -243,13 +250,9 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     # ---------------- roofline of the dominant op family (timed region) and per-op table (warm-up steps)
-    per_op = {}
-    for op, kind, a, b in warm_events[-len(ops) * len(layers):]:  # last warm-up step (the first pays one-time set-up)
-        d = per_op.setdefault(op, dict(ms=0.0, flops=0.0))
-        d["ms"] += a.elapsed_time(b)
-        d["flops"] += flops_layer[kind]
-    per_op = {k: {"ms_per_step": round(v["ms"], 4),
-                  "tflops": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 3)} for k, v in per_op.items()}
+    fam_flops = sum(flops_layer.values())  # every family runs every layer once per step
+    per_op = {op: {"ms_per_step": round(fam_ms[op], 4), "tflops": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12, 3)}
+              for op in ops}
     roofline = None
     roofline_note = None
     if events is None and not small and not args.no_events:
@@ -261,7 +264,11 @@ def main():
                                         " and ".join(([("replays a HIP graph of the same step")] if graph is not None else [])
                                                      + (["runs dalpha on a second stream"] if side is not None else []))))
     if events:
-        ms = sum(a.elapsed_time(b) for _, _, a, b in events)
+        # per step of the dominant family: median over the steps the events cover (robust against a stray slow launch)
+        per_step = len(layers)
+        step_ms = sorted(sum(a.elapsed_time(b) for _, _, a, b in events[i:i + per_step])
+                         for i in range(0, len(events) - per_step + 1, per_step))
+        ms = step_ms[(len(step_ms) - 1) // 2] * (len(events) / per_step)
         fl = sum(flops_layer[kind] for _, kind, _, _ in events)
         achieved = fl / (ms * 1e-3) / 1e12
         main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
