@@ -273,6 +273,8 @@ def main():
         achieved = fl / (ms * 1e-3) / 1e12
         main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
+        if (dom == "fwd" and T <= 80) or (dom == "bwd_input" and T <= 48):  # the library streams the planes up to there
+            main_kernel = "stream_kernel (+ quant_act_kernel), one pass over the planes per 16-token tile"
         roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
                     "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)) if not args.g else None,

@@ -141,12 +141,12 @@ bcq_status bcq_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, int
 bcq_status bcq_decode_layout_bytes(int64_t N, int64_t K, int q, size_t* out);
 bcq_status bcq_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, void* stream);
 
-/* Forward (Eq. 2) from the decode layout, for fewer than 32 tokens of bf16 activations: same result as
+/* Forward (Eq. 2) from the decode layout, for at most 80 tokens of bf16 activations: same result as
  * bcq_linear_fwd_grouped on the canonical planes.
  *   tiled: output of bcq_pack_decode, in; alpha [q][N][K/g] fp32 in (g == K: row-wise; else g % 512 == 0);
  *   x [T][K] bf16 in; y [T][N] bf16 out; workspace REQUIRED, at least
  *   bcq_workspace_bytes_grouped(BCQ_OP_FWD, T, N, K, g, q, BCQ_BF16) bytes.
- * Errors: BCQ_ERR_DTYPE for fp32 activations; BCQ_ERR_SHAPE for T >= 32 or a group size the streaming kernels do
+ * Errors: BCQ_ERR_DTYPE for fp32 activations; BCQ_ERR_SHAPE for T > 80 or a group size the streaming kernels do
  * not take; BCQ_ERR_NULL without workspace; the others as for bcq_linear_fwd. */
 bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, const void* x, int dtype, int64_t T,
                                  int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
@@ -168,8 +168,8 @@ bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, co
 /* Input gradient (Eq. 3): dx[t][k] = sum_n dy[t][n] * sum_i alpha_i[n] * B_i[n][k].
  *   packed [q][N][K/32] in; packed_t [q][K][N/32] in, may be NULL (non-NULL needs N % 32 == 0); alpha [q][N] in;
  *   dy [T][N] `dtype` in; dx [T][K] `dtype` out.
- * Below 32 tokens the fast path streams the twin and needs BOTH packed_t and the workspace; from 32 tokens on it
- * needs the workspace only and uses packed_t when given.  Without them a slower path reads `packed`. */
+ * Up to 48 tokens the fast path streams the twin and needs BOTH packed_t and the workspace; from 32 tokens on the
+ * tiled path needs the workspace only and uses packed_t when given.  Without them a slower path reads `packed`. */
 bcq_status bcq_linear_bwd_input(const uint32_t* packed, const uint32_t* packed_t, const float* alpha,
                                 const void* dy, int dtype, int64_t T, int64_t N, int64_t K, int q, void* dx,
                                 void* workspace, size_t workspace_bytes, void* stream);

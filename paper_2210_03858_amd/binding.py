@@ -206,7 +206,7 @@ def bcq_pack_decode(packed, tiled=None):
 
 
 def bcq_linear_fwd_decode(tiled, alpha, x, g=None, y=None, workspace=None):
-    """Forward from the decode layout; alpha[q,N] or [q,N,K/g]; fewer than 32 tokens of bf16; workspace required."""
+    """Forward from the decode layout; alpha[q,N] or [q,N,K/g]; at most 80 tokens of bf16; workspace required."""
     T, K = x.shape
     q, N = alpha.shape[0], alpha.shape[1]
     g = K if g is None else int(g)

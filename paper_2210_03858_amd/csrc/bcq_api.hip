@@ -66,17 +66,22 @@ bool small_bwd_alpha_ok(int64_t T, bool rowwise, int dtype) { return dtype == BC
 
 // Streaming kernels (need a workspace): row-wise scales, or group-wise scales whose groups are whole 512-column
 // segments (forward, scale gradient); the input gradient takes any group size (one activation set per plane and
-// group, at most kStreamMaxSets of them).
+// group, at most kStreamMaxSets of them).  They take one pass over the planes per 16-token tile, and up to the
+// token counts below that is still faster than expanding the weights for the tiled matrix-core kernels, whose few
+// token tiles leave most of the chip idle (measured on 7680 x 2560, 10240 x 2560, 2560 x 10240: forward 17 - 39 us
+// against 41 - 100 us at 32 - 80 tokens, input gradient 33 - 50 us against 43 - 102 us at 32 - 48 tokens).
 constexpr int64_t kStreamMaxSets = 256;
+constexpr int64_t kStreamFwdMaxTokens = 80;
+constexpr int64_t kStreamDxMaxTokens = 48;
 bool stream_group_ok(int64_t K, int64_t g) { return g == K || g % 512 == 0; }
 bool stream_fwd_ok(int64_t T, int64_t K, int64_t g, int dtype) {
-    return dtype == BCQ_BF16 && T < kMfmaMinTokens && stream_group_ok(K, g);
+    return dtype == BCQ_BF16 && T <= kStreamFwdMaxTokens && stream_group_ok(K, g);
 }
 bool stream_bwd_alpha_ok(int64_t T, int64_t K, int64_t g, int dtype) {
     return dtype == BCQ_BF16 && T <= 16 && stream_group_ok(K, g);
 }
 bool stream_bwd_input_ok(int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype) {
-    return dtype == BCQ_BF16 && T < kMfmaMinTokens && N % 32 == 0 && q * (K / g) <= kStreamMaxSets;
+    return dtype == BCQ_BF16 && T <= kStreamDxMaxTokens && N % 32 == 0 && q * (K / g) <= kStreamMaxSets;
 }
 
 bool mfma_fwd_ok(int64_t T, bool rowwise, int dtype) {
@@ -277,7 +282,7 @@ bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, cons
     s = check_group(K, g);
     if (s != BCQ_OK) return s;
     if (dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
-    if (!stream_fwd_ok(T, K, g, dtype)) return BCQ_ERR_SHAPE;  // fewer than 32 tokens; row-wise or g % 512 == 0
+    if (!stream_fwd_ok(T, K, g, dtype)) return BCQ_ERR_SHAPE;  // at most 80 tokens; row-wise or g % 512 == 0
     if (misaligned(tiled) || misaligned(alpha) || misaligned(x) || misaligned(y)) return BCQ_ERR_ALIGN;
     s = check_workspace(workspace, workspace_bytes, bcq::stream_fwd_workspace(T, K));
     if (s != BCQ_OK) return s;

@@ -124,7 +124,7 @@ def test_decode_layout_errors_before_device(lib):
     ws = 1 << 24
     assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(K), q, A, None, 0, None) == 1       # workspace required
     assert lib.bcq_linear_fwd_decode(A, A, A, 0, T, N, K, i64(K), q, A, A, ws, None) == 3         # bf16 only
-    assert lib.bcq_linear_fwd_decode(A, A, A, 1, 32, N, K, i64(K), q, A, A, ws, None) == 2        # fewer than 32 tokens
+    assert lib.bcq_linear_fwd_decode(A, A, A, 1, 81, N, K, i64(K), q, A, A, ws, None) == 2        # at most 80 tokens
     assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(96), q, A, A, ws, None) == 2        # g % 512 != 0
     assert lib.bcq_linear_fwd_decode(A, A, A, 1, T, N, K, i64(K), q, A, A, 16, None) == 5         # workspace too small
     assert lib.bcq_linear_fwd_decode(A, A, A + 2, 1, T, N, K, i64(K), q, A, A, ws, None) == 4

@@ -337,7 +337,7 @@ def test_decode_forward_rejects_what_it_does_not_take(bcq):
     tiled = torch.zeros((bcq.decode_layout_bytes(N, K, q) // 4,), dtype=torch.int32, device="cuda")
     alpha = torch.ones((q, N, 1), dtype=torch.float32, device="cuda")
     ws = torch.empty((1 << 20,), dtype=torch.uint8, device="cuda")
-    for T, dt, g, w in ((32, torch.bfloat16, K, ws), (4, torch.float32, K, ws), (4, torch.bfloat16, 256, ws),
+    for T, dt, g, w in ((81, torch.bfloat16, K, ws), (4, torch.float32, K, ws), (4, torch.bfloat16, 256, ws),
                         (4, torch.bfloat16, K, None)):
         x = torch.zeros((T, K), dtype=dt, device="cuda")
         a = alpha if g == K else torch.ones((q, N, K // g), dtype=torch.float32, device="cuda")
