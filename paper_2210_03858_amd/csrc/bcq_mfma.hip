@@ -415,6 +415,13 @@ static hipError_t launch_gemm(const bf16_t* A, int64_t lda, const u32x4* frag, b
     const int64_t tiles = ((M + 255) / 256) * ((NC + 255) / 256);
     const int64_t rounds = (tiles + 255) / 256;
     if (tiles * 10 >= rounds * 256 * 8) return launch_gemm_cfg<4, 4>(A, lda, frag, C, ldc, M, NC, R, R16, st);
+    // few tokens (a few hundred): 128 x 128 tiles would leave compute units without work; 64-token tiles fill them
+    const int64_t tiles128 = ((M + 127) / 128) * ((NC + 127) / 128);
+    if (tiles128 < 192) {
+        const int64_t tiles_64x128 = ((M + 63) / 64) * ((NC + 127) / 128);
+        if (tiles_64x128 >= 192) return launch_gemm_cfg<1, 2>(A, lda, frag, C, ldc, M, NC, R, R16, st);
+        return launch_gemm_cfg<1, 1>(A, lda, frag, C, ldc, M, NC, R, R16, st);
+    }
     return launch_gemm_cfg<2, 2>(A, lda, frag, C, ldc, M, NC, R, R16, st);
 }
 

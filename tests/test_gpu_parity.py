@@ -164,6 +164,17 @@ def test_small_shapes_ragged(bcq, oracle, dtype, T, N, K, q):
         _run_layer(bcq, oracle, 3, "out", T, N, K, q, dtype, workspace=workspace, twin=twin)
 
 
+@pytest.mark.parametrize("T,N,K,q", [
+    (130, 8448, 256, 2),   # forward: 3 x 66 tiles of 64 x 128 tokens x outputs; input gradient: 64 x 64 tiles
+    (130, 256, 8448, 3),   # the reverse
+    (200, 2560, 2560, 4),  # 64 x 128 tiles in both, ragged last token tile
+    (97, 1000, 4128, 4),   # N % 32 != 0 (no twin), K / 32 not a multiple of 4
+])
+def test_few_hundred_tokens_small_gemm_tiles(bcq, oracle, T, N, K, q):
+    """At a few hundred tokens the matrix-core path picks 64-token tiles so that the compute units have work."""
+    _run_layer(bcq, oracle, 3, "mlp_up", T, N, K, q, "bf16", workspace=True, twin=(N % 32 == 0))
+
+
 def test_q_train_and_grad_scale(bcq, oracle):
     _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "bf16", q_train=1, grad_scale=1.0 / 512, workspace=True)
     _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "f32", q_train=2, grad_scale=0.5)
