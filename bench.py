@@ -54,10 +54,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="keep the whole step on one stream.  By default (32 tokens and more, layers below 2e11 flops) the "
-                         "scale gradients run on a second HIP stream of default priority, joined at the end of the "
-                         "step: in training dalpha is a leaf of the backward pass (Eq. 4), only the optimizer waits "
-                         "for it")
+                    help="keep the whole step on one stream.  By default (32 tokens and more) the scale gradients run on "
+                         "a second HIP stream of default priority, joined at the end of the step: in training dalpha "
+                         "is a leaf of the backward pass (Eq. 4), only the optimizer waits for it")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every timed step from Python instead of replaying one captured HIP graph (a step is 32 "
                          "short launches: on a slow host the Python loop, not the GPU, then sets the pace)")
@@ -154,10 +153,7 @@ def main():
             bcq.bcq_linear_bwd_alpha_grouped(L["packed"], L["x"], L["dy"], L["g"], dalpha=L["da"],
                                              workspace=L["ws"][3])
 
-    # a second stream pays while single kernels leave part of the chip idle at their start and end; layers whose every
-    # kernel runs for a hundred microseconds and more (workload 4) gain nothing and lose L2 locality
-    big = max(2.0 * T * L["N"] * L["K"] for L in layers) > 2e11
-    side = torch.cuda.Stream() if (not args.no_overlap and not small and not big) else None
+    side = torch.cuda.Stream() if (not args.no_overlap and not small) else None
 
     def step_overlapped():
         """fwd and dx of every layer on the current stream, dalpha on the side stream; one join at the end."""
