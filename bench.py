@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # 256 compute units x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
 # HBM-side bytes per launch of the dominant kernel of the default workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy); see
@@ -271,8 +272,13 @@ def main():
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
         if (dom == "fwd" and T <= 80) or (dom == "bwd_input" and T <= 48):  # the library streams the planes up to there
             main_kernel = "stream_kernel (+ quant_act_kernel), one pass over the planes per 16-token tile"
-        roofline = {"bound": "mfma", "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
-                    "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 5),
+        bound, peak = "mfma", PEAK_BF16_MFMA_TFLOPS
+        if dtype != "bf16":
+            # fp32 activations take the any-shape vector-ALU kernels, which execute q plane products (2 q T N K lane
+            # operations for 2 T N K effective flops): priced against the fp32 vector peak of the chip
+            bound, peak, main_kernel = "alu", PEAK_FP32_VECTOR_TFLOPS, "%s_generic_kernel" % dom
+        roofline = {"bound": bound, "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 5),
                     "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)) if not args.g else None,
                     "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
                     "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
