@@ -209,3 +209,47 @@ def test_bwd_alpha_is_deterministic(bcq, oracle):
     b = bcq.bcq_linear_bwd_alpha(d_packed, d_x, d_dy, workspace=ws)
     _sync()
     assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        q = int(rng.integers(1, 9))
+        K = 32 * int(rng.integers(1, 50))
+        N = int(rng.integers(1, 520))
+        T = int(rng.choice([1, 2, 5, 8, 9, 16, 17, 31, 32, 33, 48, 49, 64, 80, 81, 100, 130]))
+        divs = [g for g in range(32, K + 1, 32) if K % g == 0]
+        g = int(rng.choice(divs))
+        dtype = "bf16" if rng.random() < 0.8 else "f32"
+        cases.append((T, N, K, g, q, dtype, bool(rng.random() < 0.8), bool(rng.random() < 0.7)))
+    return cases
+
+
+@pytest.mark.parametrize("T,N,K,g,q,dtype,workspace,twin", _random_cases(36, 20221003858))
+def test_random_shapes(bcq, oracle, T, N, K, g, q, dtype, workspace, twin):
+    """Seeded random shapes, group sizes, plane counts and call options: every dispatch boundary of the library
+    (token thresholds, tile shapes, ragged tails, with / without workspace and twin) against the oracle."""
+    import torch
+    W, alpha, planes, packed, x, dy = make_case(3, "out", T, N, K, q, dtype, oracle, g=g)
+    a3 = alpha if alpha.ndim == 3 else alpha[:, :, None]
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(a3)
+    d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
+    d_twin = bcq.bcq_pack_transposed(d_packed) if (twin and N % 32 == 0) else None
+    code = 0 if dtype == "f32" else 1
+
+    def ws(op):
+        if not workspace:
+            return None
+        return torch.empty((max(bcq.workspace_bytes_grouped(op, T, N, K, g, q, code), 16),), dtype=torch.uint8, device="cuda")
+
+    q_train = max(1, q - 1)
+    y = bcq.bcq_linear_fwd_grouped(d_packed, d_alpha, d_x, g, workspace=ws(1))
+    dx = bcq.bcq_linear_bwd_input_grouped(d_packed, d_alpha, d_dy, g, packed_t=d_twin, workspace=ws(2))
+    da = bcq.bcq_linear_bwd_alpha_grouped(d_packed, d_x, d_dy, g, q_train=q_train, grad_scale=0.25, workspace=ws(3))
+    _sync()
+    tol = tol_for(dtype)
+    ref_da = oracle.bwd_alpha(planes, x, dy, q_train=q_train, grad_scale=0.25, g=g)
+    assert nmax_err(to_host(y), oracle.fwd(alpha, planes, x)) <= tol
+    assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol
+    assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
