@@ -253,3 +253,43 @@ def test_random_shapes(bcq, oracle, T, N, K, g, q, dtype, workspace, twin):
     assert nmax_err(to_host(y), oracle.fwd(alpha, planes, x)) <= tol
     assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol
     assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
+
+
+def _random_streaming_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        q = int(rng.integers(1, 9))
+        K = int(rng.choice([512, 1024, 1536, 2048, 2560, 3072, 4096, 4608]))
+        N = 32 * int(rng.integers(1, 90))
+        T = int(rng.integers(1, 81))
+        g = int(rng.choice([K] + [d for d in (512, 1024, 1536, 2048) if d < K and K % d == 0]))
+        cases.append((T, N, K, g, q))
+    return cases
+
+
+@pytest.mark.parametrize("T,N,K,g,q", _random_streaming_cases(24, 2210))
+def test_random_streaming_shapes(bcq, oracle, T, N, K, g, q):
+    """Seeded random shapes the streaming kernels take (twin and workspace given, groups of whole segments): one to
+    five token tiles, one or several segments per wave, every plane count."""
+    import torch
+    W, alpha, planes, packed, x, dy = make_case(3, "qkv", T, N, K, q, "bf16", oracle, g=g)
+    a3 = alpha if alpha.ndim == 3 else alpha[:, :, None]
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(a3)
+    d_x, d_dy = to_dev(x, "bf16"), to_dev(dy, "bf16")
+    d_twin = bcq.bcq_pack_transposed(d_packed)
+
+    def ws(op):
+        return torch.empty((max(bcq.workspace_bytes_grouped(op, T, N, K, g, q, 1), 16),), dtype=torch.uint8, device="cuda")
+
+    y = bcq.bcq_linear_fwd_grouped(d_packed, d_alpha, d_x, g, workspace=ws(1))
+    yd = bcq.bcq_linear_fwd_decode(bcq.bcq_pack_decode(d_packed), d_alpha, d_x, g=g, workspace=ws(1))
+    dx = bcq.bcq_linear_bwd_input_grouped(d_packed, d_alpha, d_dy, g, packed_t=d_twin, workspace=ws(2))
+    da = bcq.bcq_linear_bwd_alpha_grouped(d_packed, d_x, d_dy, g, workspace=ws(3))
+    _sync()
+    tol = tol_for("bf16")
+    ref_y, ref_da = oracle.fwd(alpha, planes, x), oracle.bwd_alpha(planes, x, dy, g=g)
+    assert nmax_err(to_host(y), ref_y) <= tol
+    assert nmax_err(to_host(yd), ref_y) <= tol
+    assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol
+    assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
