@@ -36,6 +36,11 @@
  *   - Limits: 1 <= q <= 8; K % 32 == 0; 1 <= N, K <= 2^17; 1 <= T <= 2^24; N*K and T*max(N,K) at most 2^40.
  *   - No global state besides per-device capability caches; calls on different streams may overlap
  *     as long as their outputs and workspaces do not alias.
+ *   - HIP graphs: every call only launches kernels on `stream` (no allocation, no memset, no
+ *     synchronisation), so it can be recorded into a graph.  The first launch of a kernel that
+ *     needs more than 64 KiB of LDS raises that kernel's limit (a host-side attribute call), so
+ *     run each call once with its shapes before the capture.  A captured call keeps pointing at
+ *     the buffers it was recorded with.
  */
 #ifndef BCQ_H
 #define BCQ_H
