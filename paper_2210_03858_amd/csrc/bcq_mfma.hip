@@ -11,11 +11,12 @@
 //      32 output columns and every 16-long slice of the contraction, 64 lanes x 8 bf16 = 1 KiB contiguous.
 //      This scratch is transient per call; persistent storage stays q bits per weight.
 //   2. gemm_kernel: 256 x 256 output tile per workgroup, 4 waves in a 2 x 2 grid, each wave 128 x 128 =
-//      4 x 4 MFMA tiles of v_mfma_f32_32x32x16_bf16.  The activation tile goes global -> registers -> LDS
-//      (double buffered, rows padded by 16 B so that the 16-byte fragment reads are bank-conflict free); the
-//      weight fragments are loaded straight from the workspace into registers (1 KiB coalesced per wave
-//      load), so LDS carries only the activations.
+//      4 x 4 MFMA tiles of v_mfma_f32_32x32x16_bf16.  The activation tile goes global -> LDS directly
+//      (buffer_load ... lds, three stages in flight, 16-byte chunks XOR-swizzled by row so that the fragment
+//      reads are bank-conflict free); the weight fragments are loaded straight from the workspace into
+//      registers (1 KiB coalesced per wave load), so LDS carries only the activations.
 #include "bcq_internal.h"
+#include <type_traits>
 
 namespace bcq {
 
@@ -183,18 +184,20 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
 // slices per column tile (R16 * 16 >= R, a multiple of 128), C row-major bf16 with leading dimension ldc.
 // Workgroup tile (64 TM) x (64 TN), 4 waves in a 2 x 2 grid, each wave TM x TN MFMA tiles.
 // The weight fragment is the first MFMA operand, so one lane ends up with 4 consecutive output columns of
-// one token.  Out-of-range rows, chunks and column tiles are clamped to valid addresses instead of branching:
-// their products land in outputs that are never stored, or meet zero weights.
+// one token.  Nothing branches on the ragged edges: activation rows beyond M and bytes beyond the end of A come
+// back as zeros from the buffer range check, contraction indices beyond R meet zero weights, and column tiles
+// beyond NC are clamped to the last valid tile (their products are never stored).
 template <int TM, int TN>
 struct GemmCfg {
     static constexpr int BMT = 64 * TM, BNT = 64 * TN;
-    static constexpr int BKC = (TM * TN <= 4) ? 128 : 64;      // contraction per K-step: small tiles take longer steps
+    static constexpr int BKC = 64;                             // contraction per K-step
     static constexpr int KS = BKC / 16;                        // 16-slices per K-step
-    static constexpr int ROWBC = BKC * 2 + 16;                 // LDS row of the activation tile, padded by 16 B
-    static constexpr int STAGE_B = BMT * ROWBC;                // one activation stage
+    static constexpr int ROWB = BKC * 2;                       // LDS row of the activation tile (8 chunks of 16 B, swizzled)
+    static constexpr int STAGE_B = BMT * ROWB;                 // one activation stage
+    static constexpr int NST = 3;                              // stages in flight
     static constexpr int EPI_ROWB = 64 * TN + 8;               // epilogue row: 32 TN columns of bf16 + pad
     static constexpr int EPI_B = 4 * 64 * EPI_ROWB;            // 4 waves x 64 tokens
-    static constexpr int LDS_B = (2 * STAGE_B > EPI_B) ? 2 * STAGE_B : EPI_B;
+    static constexpr int LDS_B = (NST * STAGE_B > EPI_B) ? NST * STAGE_B : EPI_B;
     static constexpr int OCC = (TM * TN >= 16) ? 1 : 2;
 };
 
@@ -202,10 +205,12 @@ template <int TM, int TN>
 __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const u32x4* __restrict__ Bfrag, bf16_t* __restrict__ C, int64_t ldc,
     int64_t M, int64_t NC, int64_t R, int64_t R16, TileMap tmap) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the buffer-resource builtins exist in the device pass only
     using Cfg = GemmCfg<TM, TN>;
-    constexpr int STAGE_B = Cfg::STAGE_B, ROWBC = Cfg::ROWBC, KS = Cfg::KS, BKC = Cfg::BKC;
+    constexpr int STAGE_B = Cfg::STAGE_B, ROWB = Cfg::ROWB, KS = Cfg::KS, BKC = Cfg::BKC, NST = Cfg::NST;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps descriptors and LDS bases scalar
     const int wm = wave >> 1, wn = wave & 1;
 
     int tile_m, tile_n, copy_unused;
@@ -221,31 +226,40 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // activation tile: 64 TM rows x CPR chunks of 16 B; thread handles chunk lc of rows lr + RSTEP * j
-    constexpr int CPR = BKC / 8, RSTEP = 256 / CPR, NA = 64 * TM / RSTEP;
-    const int lc = tid % CPR, lr = tid / CPR;
-    const bf16_t* arow[NA];
+    // Activation tile: global -> LDS without passing registers (buffer_load ... lds, 16 B per lane).  One wave
+    // instruction fills 1 KiB of LDS = 8 tile rows of 128 B; lane l lands in row l / 8, slot l % 8 and fetches
+    // chunk slot ^ row of that row, so the fragment reads below (32 rows, one chunk index) are bank-conflict
+    // free without padding.  Each wave has one buffer descriptor, based at the first of its 16 TM rows and ending
+    // at the end of A, so rows beyond M read zeros; the per-lane offset is loop invariant, the 8-row group and
+    // the K-step advance through the scalar offset (below 2^31 because lda < 2^24, checked by the host).
+    static_assert(ROWB == 128, "8 chunks per row");
+    constexpr int NDMA = Cfg::BMT / 8 / 4;    // wave instructions per wave and stage
+    const int64_t steps = R16 * 16 / BKC;
+    const int64_t last = steps - 1;
+    const int64_t wrow0 = m0 + wave * NDMA * 8;
+    const int64_t left = (M - wrow0) * lda * 2;  // bytes from this wave's first row to the end of A (lda >= R)
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(A + (left > 0 ? wrow0 * lda : 0)), 0, (int)(left > 0 ? (left < 0x7fffffffll ? left : 0x7fffffffll) : 0),
+        0x00020000);
+    const int achunk = (lane & 7) ^ (lane >> 3);
+    const uint32_t voff = (uint32_t)((lane >> 3) * lda * 2 + achunk * 16);
+    // the last K-step may reach beyond R: its chunks are clamped into the row (they meet zero weights)
+    int64_t k_tail = last * BKC + achunk * 8;
+    k_tail = k_tail < R - 8 ? k_tail : R - 8;
+    const uint32_t voff_tail = (uint32_t)((lane >> 3) * lda * 2 + k_tail * 2);
+    const int group_b = (int)(8 * lda * 2);   // bytes between two 8-row groups
+    auto dma_a = [&](int64_t step, int stage) {
+        const bool tail = step >= last;
+        const uint32_t vo = tail ? voff_tail : voff;
+        const int so = tail ? 0 : (int)(step * BKC * 2);
 #pragma unroll
-    for (int j = 0; j < NA; ++j) {
-        int64_t row = m0 + lr + RSTEP * j;
-        row = row < M ? row : M - 1;
-        arow[j] = A + row * lda;
-    }
-    const int64_t kmax = R - 8;
-    u32x4 areg[NA];
-    auto load_a = [&](int64_t k0) {
-        int64_t k = k0 + lc * 8;
-        k = k < kmax ? k : kmax;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) areg[j] = *reinterpret_cast<const u32x4*>(arow[j] + k);
-    };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < NA; ++j)
-            *reinterpret_cast<u32x4*>(smem + buf * STAGE_B + (lr + RSTEP * j) * ROWBC + lc * 16) = areg[j];
+        for (int j = 0; j < NDMA; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rsrc, (void __attribute__((address_space(3)))*)(smem + stage * STAGE_B + (wave * NDMA + j) * 1024), 16,
+                vo, so + j * group_b, 0, 0);
     };
 
-    // weight fragments of this wave: column tiles ct0 .. ct0+TN-1
+    // weight fragments of this wave: column tiles ct0 .. ct0+TN-1, straight from global memory into registers
     const int64_t ct0 = (n0 + wn * 32 * TN) / 32;
     const u32x4* bptr[TN];
 #pragma unroll
@@ -259,59 +273,111 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[kk][j] = bptr[j][(step * KS + kk) * 64];
     };
-    bf16x8 xf[2][TM];  // activation fragments of two consecutive 16-slices
-    auto read_x = [&](int buf, int kk) {
-        const unsigned char* sa =
-            smem + buf * STAGE_B + (wm * 32 * TM + (lane & 31)) * ROWBC + (lane >> 5) * 16 + kk * 32;
+
+    // Fragment reads are inline assembly: the compiler guards every LDS read it sees that may alias a direct-to-LDS
+    // load with a wait for ALL outstanding loads.  wait_x / wait_stage tie the fragment registers to an explicit
+    // s_waitcnt, so no consumer can be scheduled above the wait.
+    u32x4 xf[2][TM];  // activation fragments of two consecutive 16-slices
+    // lane (r = lane % 32, h = lane / 32) takes chunk 2 kk + h of row wm * 32 TM + 32 i + r
+    const int xrow = wm * 32 * TM + (lane & 31);
+    uint32_t xoff[KS];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) xf[kk & 1][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * ROWBC);
+    for (int kk = 0; kk < KS; ++kk)
+        xoff[kk] = (uint32_t)(xrow * ROWB + (((2 * kk + (lane >> 5)) ^ (xrow & 7)) * 16));  // 32 i keeps row & 7
+    auto read_x = [&](int stage, int kk) {
+        const uint32_t addr = xoff[kk] + (uint32_t)(stage * STAGE_B);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(xf[kk & 1][i]) : "v"(addr), "n"(i * 32 * ROWB));
+    };
+    // gfx9 s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
+    auto wait_regs = [&](int kk, auto imm) {
+        constexpr int IMM = decltype(imm)::value;
+        u32x4* f = xf[kk & 1];
+        if constexpr (TM == 4)
+            asm volatile("s_waitcnt %4" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(IMM) : "memory");
+        else if constexpr (TM == 2)
+            asm volatile("s_waitcnt %2" : "+v"(f[0]), "+v"(f[1]) : "n"(IMM) : "memory");
+        else
+            asm volatile("s_waitcnt %1" : "+v"(f[0]) : "n"(IMM) : "memory");
+    };
+    // the fragments of slice kk are usable once only the TM reads of the following slice are outstanding
+    auto wait_x = [&](int kk) { wait_regs(kk, std::integral_constant<int, 63 | (3 << 14) | (7 << 4) | (TM << 8)>()); };
+    // Before the barrier of a K-step: every LDS read of this wave has returned (the stage may be refilled after
+    // the barrier) and this wave's part of the next stage has landed.  That stage was requested a whole K-step
+    // ago and loads complete in order, so it is enough that at most the loads issued during this K-step (the
+    // fill and KS - 1 slices of weights) remain in flight - which the coming MFMAs need anyway.
+    auto wait_stage = [&](int kk) {
+        constexpr int MAXV = NDMA + (KS - 1) * TN;
+        wait_regs(kk, std::integral_constant<int, (MAXV & 15) | ((MAXV >> 4) << 14) | (7 << 4) | (0 << 8)>());
     };
     auto mfma_slice = [&](int kk) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), xf[kk & 1][i], acc[j][i], 0, 0, 0);
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[kk][j]), as_bf16x8(xf[kk & 1][i]),
+                                                                    acc[j][i], 0, 0, 0);
     };
 
-    const int64_t steps = R16 * 16 / BKC;
-    const int64_t last = steps - 1;
-    load_a(0);
+    // Prologue: stages 0 .. NST-2 requested, then the weights of step 0.  These first weight loads are inline
+    // assembly as well, so that they are issued HERE, in flight together with the activation stages (the
+    // compiler would sink them below the barrier); tie_b makes them usable.
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) load_b(kk, 0);
-    store_a(0);
-    __syncthreads();
+    for (int p = 0; p < NST - 1; ++p) dma_a(p, p);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(b[kk][j]) : "v"(bptr[j]), "n"(kk * 1024));
+    {
+        constexpr int MAXV = (NST - 2) * NDMA + KS * TN;  // stage 0 has landed (this wave's part)
+        asm volatile("s_waitcnt %0" ::"n"((MAXV & 15) | ((MAXV >> 4) << 14) | (7 << 4) | (15 << 8)) : "memory");
+    }
+    __builtin_amdgcn_s_barrier();
     read_x(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {  // all prologue loads have returned
+        u32x4* f = b[kk];
+        if constexpr (TN == 4)
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3])::"memory");
+        else if constexpr (TN == 2)
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(f[0]), "+v"(f[1])::"memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(f[0])::"memory");
+    }
 
-    // One K-step = KS 16-slices.  All but the last: issue the LDS reads of the next slice, the MFMAs of this one,
-    // then refill this slice's weight registers for the next K-step (a full step of latency cover).  The LDS
-    // hand-over to the next stage (write, barrier, first fragment read) sits BEFORE the MFMAs of the last slice,
+    // One K-step = KS 16-slices.  At its start the stage NST - 1 steps ahead is requested into the buffer that was
+    // read during the previous step.  Per slice: issue the LDS reads of the next slice, the MFMAs of this one,
+    // then refill this slice's weight registers for the next K-step (a full step of latency cover).  The
+    // hand-over to the next stage (wait, barrier, first fragment read) sits BEFORE the MFMAs of the last slice,
     // whose operands are already in registers, so the matrix pipe stays busy across the barrier.
+    int st = 0;  // stage of step s
     for (int64_t s = 0; s < steps; ++s) {
-        const int buf = (int)(s & 1);
         const int64_t nx = s < last ? s + 1 : last;
-        load_a(nx * BKC);
+        const int st_next = (st + 1 == NST) ? 0 : st + 1;
+        const int st_fill = (st == 0) ? NST - 1 : st - 1;
+        dma_a(s + NST - 1, st_fill);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < KS - 1; ++kk) {
-            read_x(buf, kk + 1);
+            read_x(st, kk + 1);
+            wait_x(kk);
             mfma_slice(kk);
             load_b(kk, nx);
-            __builtin_amdgcn_sched_group_barrier(0x100, TM, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        store_a(buf ^ 1);
-        __syncthreads();
-        read_x(buf ^ 1, 0);
+        wait_stage(KS - 1);
+        __builtin_amdgcn_s_barrier();
+        read_x(st_next, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfma_slice(KS - 1);
         load_b(KS - 1, nx);
-        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, TN, 0);
         __builtin_amdgcn_sched_barrier(0);
+        st = st_next;
     }
+    // the clamped requests of the last steps are still writing LDS, and the last fragment read is in flight
+    wait_regs(0, std::integral_constant<int, 0 | (7 << 4)>());
 
     // epilogue: acc register 4g+e of lane l is weight column 8g + 4*(l/32) + e, token l%32 of its 32 x 32 tile.
     // Pass the tile through LDS (64 tokens per wave at a time) so that global stores are 16 B per lane and
@@ -380,6 +446,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
                 }
         }
     }
+#endif
 }
 
 static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
