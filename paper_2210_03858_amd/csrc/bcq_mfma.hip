@@ -388,9 +388,12 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
         unsigned char* ew = smem + wave * 64 * EROW;
         constexpr int CH = 4 * TN;        // 16-byte chunks per row
         constexpr int RPI = 64 / CH;      // rows per store instruction
+        __syncthreads();  // every wave is done with the activation stages; from here on a wave touches only its own region
 #pragma unroll
         for (int pass = 0; pass < (TM + 1) / 2; ++pass) {
-            __syncthreads();
+            // LDS executes one wave's instructions in order: between its own writes and reads of its region only the
+            // compiler has to keep the order
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 #pragma unroll
             for (int il = 0; il < 2; ++il) {
                 const int it = pass * 2 + il;
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
                         }
                 }
             }
-            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             const int rows_here = (TM - pass * 2 >= 2) ? 64 : 32;
             const int ch = lane % CH, r0 = lane / CH;
 #pragma unroll
@@ -614,20 +617,35 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
     int64_t lcol = (XG ? n0 : k0) + cb * 8;
     lcol = lcol < lcols - 8 ? lcol : lcols - 8;  // clamped columns only feed outputs that are never stored
     u32x4 lr[8];
+    // rows of one step: uniform base (advances by 64 rows per step) + 32-bit lane offset + r rows
+    const uint32_t row_b = (uint32_t)(ldl * 2);
+    const uint32_t voff0 = (uint32_t)(tb * 8) * row_b + (uint32_t)(lcol * 2);
     auto load_blocks = [&](int64_t step) {
+        const int64_t t0 = (step0 + step) * 64;
+        const unsigned char* base = reinterpret_cast<const unsigned char*>(L + t0 * ldl);
+        if (t0 + 64 <= T) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            int64_t t = (step0 + step) * 64 + tb * 8 + r;
-            t = t < T ? t : T - 1;  // such rows meet zero fragments of the other operand
-            lr[r] = *reinterpret_cast<const u32x4*>(L + t * ldl + lcol);
+            for (int r = 0; r < 8; ++r) lr[r] = *reinterpret_cast<const u32x4*>(base + (voff0 + (uint32_t)r * row_b));
+        } else {  // last, ragged step: rows beyond T are clamped (they meet zero fragments of the other operand)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                int64_t t = t0 + tb * 8 + r;
+                t = t < T ? t : T - 1;
+                lr[r] = *reinterpret_cast<const u32x4*>(L + t * ldl + lcol);
+            }
         }
     };
-    auto store_blocks = [&](int buf) {
-        unsigned char* sl = smem + buf * DA_STAGE;
-        u32x4 o[8];
-        transpose8x8(lr, o);
+    // column c of this thread's 8 x 8 block: 8 tokens of one column = one 16-byte LDS chunk (4 v_perm + 1 write)
+    auto store_col = [&](int buf, int c) {
+        u32x4 o;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(sl + da_swz(cb * 8 + c, tb)) = o[c];
+        for (int w = 0; w < 4; ++w)
+            o[w] = __builtin_amdgcn_perm(lr[2 * w + 1][c >> 1], lr[2 * w][c >> 1], (c & 1) ? 0x07060302u : 0x05040100u);
+        *reinterpret_cast<u32x4*>(smem + buf * DA_STAGE + da_swz(cb * 8 + c, tb)) = o;
+    };
+    auto store_blocks = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) store_col(buf, c);
     };
     bf16x8 lf[2][4];
     const int lbase = (XG ? wn : wm) * 128 + (lane & 31);
@@ -652,33 +670,52 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int j = 0; j < 4; ++j) g[kk][j] = gptr[j][(step * 4 + kk) * 64];
     };
+    auto mfma_one = [&](int kk, int i, int j) {
+        if (XG)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(g[kk][i]), lf[kk & 1][j], acc[i][j], 0, 0, 0);
+        else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[kk & 1][i], as_bf16x8(g[kk][j]), acc[i][j], 0, 0, 0);
+    };
     auto mfma_slice = [&](int kk) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (XG)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(g[kk][i]), lf[kk & 1][j], acc[i][j], 0, 0, 0);
-                else
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[kk & 1][i], as_bf16x8(g[kk][j]), acc[i][j], 0, 0, 0);
-            }
+            for (int j = 0; j < 4; ++j) mfma_one(kk, i, j);
     };
 
+    // Three LDS stages.  The blocks of step s + 1 are requested during step s - 1, transposed and written into
+    // their stage during the FIRST slice of step s, interleaved with its MFMAs (a stage is free from the barrier
+    // that ends the step after its last read), and read from the barrier that ends step s: the global latency
+    // has a whole step of cover and neither the transposes nor the LDS writes wait in front of a barrier.
     const int64_t last = steps - 1;
     load_blocks(0);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) load_g(kk, 0);
+    load_g(0, 0);
     store_blocks(0);
+    load_blocks(last < 1 ? last : 1);  // followed by three slices of fragment loads, as in every step of the loop
+#pragma unroll
+    for (int kk = 1; kk < 4; ++kk) load_g(kk, 0);
     __syncthreads();
     read_frags(0, 0);
+    int stg = 0;  // stage of step s
     for (int64_t s = 0; s < steps; ++s) {
-        const int buf = (int)(s & 1);
         const int64_t nx = s < last ? s + 1 : last;
-        load_blocks(nx);
+        const int64_t nx2 = s + 2 < steps ? s + 2 : last;
+        const int stg_next = (stg == 2) ? 0 : stg + 1;
+        read_frags(stg, 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-            read_frags(buf, kk + 1);
+        for (int c = 0; c < 8; ++c) {  // two MFMAs (64 clocks of the matrix pipe) cover one column's perms and write
+            mfma_one(0, c >> 1, 2 * (c & 1));
+            mfma_one(0, c >> 1, 2 * (c & 1) + 1);
+            store_col(stg_next, c);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_g(0, nx);
+        load_blocks(nx2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 1; kk < 3; ++kk) {
+            read_frags(stg, kk + 1);
             mfma_slice(kk);
             load_g(kk, nx);
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -686,21 +723,22 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
             __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        store_blocks(buf ^ 1);
         __syncthreads();
-        read_frags(buf ^ 1, 0);
+        read_frags(stg_next, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfma_slice(3);
         load_g(3, nx);
         __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
         __builtin_amdgcn_sched_barrier(0);
+        stg = stg_next;
     }
     __syncthreads();
 
     // epilogue: signed sums over this wave's 128 k for each plane; lane owns n = n_base + j*32 + lane%32.
     // All packed words of all trained planes are requested first (one memory latency instead of one per plane);
-    // a sign is applied by XOR-ing the (inverted) plane bit into the fp32 sign bit: shift, bit-op, add per value.
+    // a sign is applied as a factor +-1.0 built from the (inverted) plane bit: shift, and-or, fused multiply-add
+    // per value (the product with +-1.0 is exact, so this equals adding the signed value).
     float* red = reinterpret_cast<float*>(smem);  // [plane][wm][256 n]
     const int64_t Kw = K / 32;
     uint32_t words[QT][4][4];  // [plane][k tile][n tile], already inverted and shifted to this lane's rows
@@ -743,10 +781,10 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int bit = 8 * (v >> 2) + (v & 3);
-                        const uint32_t a = __float_as_uint(acc[i][j][v]);
+                        const float a = acc[i][j][v];
 #pragma unroll
                         for (int p = 0; p < QT; ++p)
-                            fs[p][j] += __uint_as_float(a ^ ((words[p][i][j] << (31 - bit)) & 0x80000000u));
+                            fs[p][j] = __builtin_fmaf(a, __uint_as_float(((words[p][i][j] << (31 - bit)) & 0x80000000u) | 0x3f800000u), fs[p][j]);
                     }
             }
 #pragma unroll
@@ -790,10 +828,10 @@ __global__ __launch_bounds__(256, 1) void dalpha_kernel(const bf16_t* __restrict
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int bit = 8 * (v >> 2) + (v & 3);
-                    const uint32_t a = __float_as_uint(acc[i][j][v]);
+                    const float a = acc[i][j][v];
 #pragma unroll
                     for (int p = 0; p < QT; ++p)  // sign bit set where the plane bit is 0 (-1): words are inverted
-                        sums[p][j] += __uint_as_float(a ^ ((words[p][i][j] << (31 - bit)) & 0x80000000u));
+                        sums[p][j] = __builtin_fmaf(a, __uint_as_float(((words[p][i][j] << (31 - bit)) & 0x80000000u) | 0x3f800000u), sums[p][j]);
                 }
         }
     }
@@ -905,7 +943,7 @@ size_t mfma_bwd_alpha_workspace(int64_t T, int64_t N, int64_t K, int64_t g, int 
 hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const void* dy, int64_t T, int64_t N,
                                  int64_t K, int64_t g, int q, int q_train, float grad_scale, float* dalpha,
                                  void* workspace, const AdamWArgs* opt, hipStream_t st) {
-    const int lds = 2 * DA_STAGE;
+    const int lds = 3 * DA_STAGE;
     const DalphaPlan pl = dalpha_plan(T, N, K, g, q);
     u32x4* frag = reinterpret_cast<u32x4*>(workspace);
     float* part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + pl.frag_bytes);
