@@ -228,8 +228,8 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
 
     // Activation tile: global -> LDS without passing registers (buffer_load ... lds, 16 B per lane).  One wave
     // instruction fills 1 KiB of LDS = 8 tile rows of 128 B; lane l lands in row l / 8, slot l % 8 and fetches
-    // chunk slot ^ row of that row, so the fragment reads below (32 rows, one chunk index) are bank-conflict
-    // free without padding.  Each wave has one buffer descriptor, based at the first of its 16 TM rows and ending
+    // the chunk that the swizzle below assigns to that slot, so the fragment reads (32 rows, one chunk index) are
+    // bank-conflict free without padding.  Each wave has one buffer descriptor, based at the first of its 16 TM rows and ending
     // at the end of A, so rows beyond M read zeros; the per-lane offset is loop invariant, the 8-row group and
     // the K-step advance through the scalar offset (below 2^31 because lda < 2^24, checked by the host).
     static_assert(ROWB == 128, "8 chunks per row");
@@ -241,22 +241,30 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(A + (left > 0 ? wrow0 * lda : 0)), 0, (int)(left > 0 ? (left < 0x7fffffffll ? left : 0x7fffffffll) : 0),
         0x00020000);
-    const int achunk = (lane & 7) ^ (lane >> 3);
-    const uint32_t voff = (uint32_t)((lane >> 3) * lda * 2 + achunk * 16);
-    // the last K-step may reach beyond R: its chunks are clamped into the row (they meet zero weights)
-    int64_t k_tail = last * BKC + achunk * 8;
-    k_tail = k_tail < R - 8 ? k_tail : R - 8;
-    const uint32_t voff_tail = (uint32_t)((lane >> 3) * lda * 2 + k_tail * 2);
+    // chunk held by slot s of tile row r: s ^ (r & 7) ^ ((r >> 3) & 1).  The last term separates rows r and r + 8,
+    // which start 1 KiB = four passes over the 64 banks apart and would otherwise meet in the same banks when 16
+    // lanes read one chunk index of 16 consecutive rows.  It alternates between consecutive 8-row groups.
+    static_assert(NDMA % 2 == 0, "the 8-row group parity is the instruction parity");
+    uint32_t voff[2], voff_tail[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int achunk = (lane & 7) ^ (lane >> 3) ^ par;
+        voff[par] = (uint32_t)((lane >> 3) * lda * 2 + achunk * 16);
+        // the last K-step may reach beyond R: its chunks are clamped into the row (they meet zero weights)
+        int64_t k_tail = last * BKC + achunk * 8;
+        k_tail = k_tail < R - 8 ? k_tail : R - 8;
+        voff_tail[par] = (uint32_t)((lane >> 3) * lda * 2 + k_tail * 2);
+    }
     const int group_b = (int)(8 * lda * 2);   // bytes between two 8-row groups
     auto dma_a = [&](int64_t step, int stage) {
         const bool tail = step >= last;
-        const uint32_t vo = tail ? voff_tail : voff;
+        const uint32_t vo0 = tail ? voff_tail[0] : voff[0], vo1 = tail ? voff_tail[1] : voff[1];
         const int so = tail ? 0 : (int)(step * BKC * 2);
 #pragma unroll
         for (int j = 0; j < NDMA; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc, (void __attribute__((address_space(3)))*)(smem + stage * STAGE_B + (wave * NDMA + j) * 1024), 16,
-                vo, so + j * group_b, 0, 0);
+                (j & 1) ? vo1 : vo0, so + j * group_b, 0, 0);
     };
 
     // weight fragments of this wave: column tiles ct0 .. ct0+TN-1, straight from global memory into registers
@@ -283,7 +291,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     uint32_t xoff[KS];
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk)
-        xoff[kk] = (uint32_t)(xrow * ROWB + (((2 * kk + (lane >> 5)) ^ (xrow & 7)) * 16));  // 32 i keeps row & 7
+        xoff[kk] = (uint32_t)(xrow * ROWB + (((2 * kk + (lane >> 5)) ^ (xrow & 7) ^ ((xrow >> 3) & 1)) * 16));  // + 32 i keeps both terms
     auto read_x = [&](int stage, int kk) {
         const uint32_t addr = xoff[kk] + (uint32_t)(stage * STAGE_B);
 #pragma unroll
