@@ -190,9 +190,9 @@ __global__ __launch_bounds__(256) void expand_bwd_kernel(const uint32_t* __restr
 template <int TM, int TN>
 struct GemmCfg {
     static constexpr int BMT = 64 * TM, BNT = 64 * TN;
-    static constexpr int BKC = 64;                             // contraction per K-step
+    static constexpr int BKC = (TM * TN <= 2) ? 128 : 64;      // contraction per K-step: 64-token tiles take longer steps
     static constexpr int KS = BKC / 16;                        // 16-slices per K-step
-    static constexpr int ROWB = BKC * 2;                       // LDS row of the activation tile (8 chunks of 16 B, swizzled)
+    static constexpr int ROWB = BKC * 2;                       // LDS row of the activation tile (8 or 16 swizzled chunks of 16 B)
     static constexpr int STAGE_B = BMT * ROWB;                 // one activation stage
     static constexpr int NST = 3;                              // stages in flight
     static constexpr int EPI_ROWB = 64 * TN + 8;               // epilogue row: 32 TN columns of bf16 + pad
@@ -227,44 +227,52 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // Activation tile: global -> LDS without passing registers (buffer_load ... lds, 16 B per lane).  One wave
-    // instruction fills 1 KiB of LDS = 8 tile rows of 128 B; lane l lands in row l / 8, slot l % 8 and fetches
-    // the chunk that the swizzle below assigns to that slot, so the fragment reads (32 rows, one chunk index) are
-    // bank-conflict free without padding.  Each wave has one buffer descriptor, based at the first of its 16 TM rows and ending
-    // at the end of A, so rows beyond M read zeros; the per-lane offset is loop invariant, the 8-row group and
-    // the K-step advance through the scalar offset (below 2^31 because lda < 2^24, checked by the host).
-    static_assert(ROWB == 128, "8 chunks per row");
-    constexpr int NDMA = Cfg::BMT / 8 / 4;    // wave instructions per wave and stage
+    // instruction fills 1 KiB of LDS = RPB tile rows of CPR chunks; lane l lands in row l / CPR, slot l % CPR and
+    // fetches the chunk that the swizzle assigns to that slot, so the fragment reads (16 lanes: one chunk index of
+    // 16 consecutive rows) are bank-conflict free without padding:
+    //   128-byte rows: slot = chunk ^ (r & 7) ^ ((r >> 3) & 1)   (rows r and r + 8 lie four passes over the 64
+    //                                                              banks apart and would meet in the same banks)
+    //   256-byte rows: slot = chunk ^ (r & 15)                    (every row starts at bank 0)
+    // Each wave has one buffer descriptor, based at the first of its 16 TM rows and ending at the end of A, so
+    // rows beyond M read zeros; the per-lane offset is loop invariant up to the swizzle term of the row group
+    // (NV variants), the row group and the K-step advance through the scalar offset (below 2^31 because
+    // lda < 2^24, checked by the host).
+    constexpr int CPR = ROWB / 16;             // chunks per row
+    constexpr int RPB = 64 / CPR;              // rows per wave instruction
+    constexpr int NDMA = Cfg::BMT / RPB / 4;   // wave instructions per wave and stage
+    constexpr int NV = (CPR == 8) ? 2 : 4;     // distinct swizzle terms of a row group: (j & 1) or (j & 3) << 2
+    static_assert(CPR == 8 || CPR == 16, "128- or 256-byte rows");
+    static_assert(NDMA % NV == 0, "the row-group term depends on the instruction index only");
     const int64_t steps = R16 * 16 / BKC;
     const int64_t last = steps - 1;
-    const int64_t wrow0 = m0 + wave * NDMA * 8;
+    const int64_t wrow0 = m0 + wave * NDMA * RPB;
     const int64_t left = (M - wrow0) * lda * 2;  // bytes from this wave's first row to the end of A (lda >= R)
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(A + (left > 0 ? wrow0 * lda : 0)), 0, (int)(left > 0 ? (left < 0x7fffffffll ? left : 0x7fffffffll) : 0),
         0x00020000);
-    // chunk held by slot s of tile row r: s ^ (r & 7) ^ ((r >> 3) & 1).  The last term separates rows r and r + 8,
-    // which start 1 KiB = four passes over the 64 banks apart and would otherwise meet in the same banks when 16
-    // lanes read one chunk index of 16 consecutive rows.  It alternates between consecutive 8-row groups.
-    static_assert(NDMA % 2 == 0, "the 8-row group parity is the instruction parity");
-    uint32_t voff[2], voff_tail[2];
+    const int drow = lane / CPR, dslot = lane % CPR;
+    uint32_t voff[NV], voff_tail[NV];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const int achunk = (lane & 7) ^ (lane >> 3) ^ par;
-        voff[par] = (uint32_t)((lane >> 3) * lda * 2 + achunk * 16);
+    for (int v = 0; v < NV; ++v) {
+        const int achunk = dslot ^ drow ^ ((CPR == 8) ? v : (v << 2));
+        voff[v] = (uint32_t)(drow * lda * 2 + achunk * 16);
         // the last K-step may reach beyond R: its chunks are clamped into the row (they meet zero weights)
         int64_t k_tail = last * BKC + achunk * 8;
         k_tail = k_tail < R - 8 ? k_tail : R - 8;
-        voff_tail[par] = (uint32_t)((lane >> 3) * lda * 2 + k_tail * 2);
+        voff_tail[v] = (uint32_t)(drow * lda * 2 + k_tail * 2);
     }
-    const int group_b = (int)(8 * lda * 2);   // bytes between two 8-row groups
+    const int group_b = (int)(RPB * lda * 2);   // bytes between two row groups
     auto dma_a = [&](int64_t step, int stage) {
         const bool tail = step >= last;
-        const uint32_t vo0 = tail ? voff_tail[0] : voff[0], vo1 = tail ? voff_tail[1] : voff[1];
+        uint32_t vo[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) vo[v] = tail ? voff_tail[v] : voff[v];
         const int so = tail ? 0 : (int)(step * BKC * 2);
 #pragma unroll
         for (int j = 0; j < NDMA; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc, (void __attribute__((address_space(3)))*)(smem + stage * STAGE_B + (wave * NDMA + j) * 1024), 16,
-                (j & 1) ? vo1 : vo0, so + j * group_b, 0, 0);
+                vo[j % NV], so + j * group_b, 0, 0);
     };
 
     // weight fragments of this wave: column tiles ct0 .. ct0+TN-1, straight from global memory into registers
@@ -288,10 +296,11 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     u32x4 xf[2][TM];  // activation fragments of two consecutive 16-slices
     // lane (r = lane % 32, h = lane / 32) takes chunk 2 kk + h of row wm * 32 TM + 32 i + r
     const int xrow = wm * 32 * TM + (lane & 31);
+    const int xswz = (CPR == 8) ? ((xrow & 7) ^ ((xrow >> 3) & 1)) : (xrow & 15);  // the same for rows 32 i further on
     uint32_t xoff[KS];
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk)
-        xoff[kk] = (uint32_t)(xrow * ROWB + (((2 * kk + (lane >> 5)) ^ (xrow & 7) ^ ((xrow >> 3) & 1)) * 16));  // + 32 i keeps both terms
+        xoff[kk] = (uint32_t)(xrow * ROWB + (((2 * kk + (lane >> 5)) ^ xswz) * 16));
     auto read_x = [&](int stage, int kk) {
         const uint32_t addr = xoff[kk] + (uint32_t)(stage * STAGE_B);
 #pragma unroll
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 16 ? 1 : 2)) void gemm_kernel(
     for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(b[kk][j]) : "v"(bptr[j]), "n"(kk * 1024));
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(b[kk][j]) : "v"(bptr[j] + kk * 64));
     {
         constexpr int MAXV = (NST - 2) * NDMA + KS * TN;  // stage 0 has landed (this wave's part)
         asm volatile("s_waitcnt %0" ::"n"((MAXV & 15) | ((MAXV >> 4) << 14) | (7 << 4) | (15 << 8)) : "memory");
