@@ -175,6 +175,31 @@ def test_few_hundred_tokens_small_gemm_tiles(bcq, oracle, T, N, K, q):
     _run_layer(bcq, oracle, 3, "mlp_up", T, N, K, q, "bf16", workspace=True, twin=(N % 32 == 0))
 
 
+@pytest.mark.parametrize("T,N,K", [(100, 96, 96), (130, 160, 224), (257, 64, 32)])
+def test_nonfinite_token_row_stays_in_its_row(bcq, oracle, T, N, K):
+    """Tiled kernels pad the contraction to a multiple of 128 and the token tile to 64 or more rows: what they read
+    for the padding must never bring another token's values into a row.  One token row of x and of dy is set to
+    +inf; every other output row must still match the oracle (which never sees the poisoned rows)."""
+    import torch
+    q, bad = 3, 7
+    W, alpha, planes, packed, x, dy = make_case(3, "out", T, N, K, q, "bf16", oracle)
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha)
+    d_twin = bcq.bcq_pack_transposed(d_packed)
+    xp, dyp = x.copy(), dy.copy()
+    xp[bad, :] = np.inf
+    dyp[bad, :] = np.inf
+    ws = lambda op: torch.empty((max(bcq.workspace_bytes(op, T, N, K, q, 1), 16),), dtype=torch.uint8, device="cuda")
+    y = to_host(bcq.bcq_linear_fwd(d_packed, d_alpha, to_dev(xp, "bf16"), workspace=ws(1)))
+    dx = to_host(bcq.bcq_linear_bwd_input(d_packed, d_alpha, to_dev(dyp, "bf16"), packed_t=d_twin, workspace=ws(2)))
+    _sync()
+    keep = np.arange(T) != bad
+    assert np.isfinite(y[keep]).all() and np.isfinite(dx[keep]).all()
+    assert not np.isfinite(y[bad]).any() and not np.isfinite(dx[bad]).any()
+    tol = tol_for("bf16")
+    assert nmax_err(y[keep], oracle.fwd(alpha, planes, x)[keep]) <= tol
+    assert nmax_err(dx[keep], oracle.bwd_input(alpha, planes, dy)[keep]) <= tol
+
+
 def test_q_train_and_grad_scale(bcq, oracle):
     _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "bf16", q_train=1, grad_scale=1.0 / 512, workspace=True)
     _run_layer(bcq, oracle, 2, "out", 64, 256, 512, 4, "f32", q_train=2, grad_scale=0.5)
