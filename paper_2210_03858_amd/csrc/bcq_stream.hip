@@ -619,6 +619,9 @@ __device__ __forceinline__ void stream_finish(q_f32x4 (&acc)[QP], float (&ep)[QP
 // ring of LCS register sets addressed by the unrolled position, LCS - 1 segments ahead of the multiplication (a
 // register move would have to wait for the load it copies).  Needs cw % 4 == 0.
 // EXACT: every part has spp segments and spp % LCS == 0 - no guards in the loop.
+// Input gradient (STREAM_DX, row-wise scales): every plane has its own scaled activations, so nothing of the operand
+// is shared between planes and the call is a one-plane forward over q * segs_n VIRTUAL segments of the transposed
+// twin: virtual segment v = plane v / segs_n, segment v % segs_n (the division is a multiplication by seg_magic).
 constexpr int LCS = 4;
 
 // 32 signs of a packed word -> the four FP4 operand registers of a lane (+1 = 0x2, -1 = 0xA; registers 4 .. 7 of the
@@ -639,8 +642,10 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
                                                           const float* __restrict__ alpha,
                                                           const bf16_t* __restrict__ dy, void* __restrict__ out,
                                                           int64_t T, int64_t rows, int64_t cw, int q_used, float scale,
-                                                          int spp, int64_t segs, int gsegs, int G) {
-    static_assert(MODE != STREAM_DX, "forward and scale gradient only");
+                                                          int spp, int64_t segs, int gsegs, int G, int64_t xq_plane,
+                                                          int64_t sq_plane, uint32_t seg_magic, int segs_n) {
+    constexpr bool DX = (MODE == STREAM_DX);
+    static_assert(!DX || (QP == 1 && !GROUPED && !TILED), "input gradient: one virtual plane, row-wise scales, twin layout");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int H = TWO ? 2 : 1, RW = 8 / KW, PF = LCS - 1;
     constexpr int XPART = LCS * 4 * H * QBLK, XBUF = KW * XPART;  // operand blocks of one part / of one buffer
@@ -683,13 +688,21 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
         if (MODE == STREAM_FWD) {
 #pragma unroll
             for (int i = 0; i < QP; ++i) ep[i][v] = (!GROUPED && i < q_used) ? alpha[(int64_t)i * rows + n] : 0.f;
+        } else if (DX) {
+            ep[0][v] = 0.f;  // unused: the scales are part of the activations
         } else {
             ep[0][v] = (tok_live && n_live) ? bf16_to_f32(dy[tok * rows + n]) : 0.f;
         }
     }
 
-    const unsigned char* xqt = xq + (size_t)tile * segs * 4 * H * QBLK;
-    const unsigned char* sqt = sq + (size_t)tile * segs * H * QSCL;
+    // DX: a set of activations per plane, [plane][token tile][segment]
+    const int64_t segs_tile = DX ? segs_n : segs;
+    const unsigned char* xqt = xq + (size_t)tile * segs_tile * 4 * H * QBLK;
+    const unsigned char* sqt = sq + (size_t)tile * segs_tile * H * QSCL;
+    auto split = [&](int vseg, int& pl_i, int& sg) {  // virtual segment -> plane, segment
+        pl_i = (int)(((uint64_t)(uint32_t)vseg * seg_magic) >> 32);
+        sg = vseg - pl_i * segs_n;
+    };
     const int part_begin = kp * spp;
     int part_end = part_begin + spp;
     part_end = part_end < (int)segs ? part_end : (int)segs;
@@ -705,13 +718,27 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
             const int p = it / (LCS * H), r = it % (LCS * H);  // part, 8 KiB slab of its chunk
             int seg = p * spp + c * LCS + r / H;
             if (!EXACT) seg = seg < last_seg ? seg : last_seg;  // in bounds; segments beyond a part are never multiplied
-            stg[it] = *reinterpret_cast<const q_u32x4*>(xqt + (size_t)seg * (4 * H * QBLK) + (r % H) * 8192 + tid * 16);
+            const unsigned char* src = xqt;
+            if (DX) {
+                int pl_i, sg;
+                split(seg, pl_i, sg);
+                src += (size_t)pl_i * xq_plane;
+                seg = sg;
+            }
+            stg[it] = *reinterpret_cast<const q_u32x4*>(src + (size_t)seg * (4 * H * QBLK) + (r % H) * 8192 + tid * 16);
         }
         if (tid < NSU) {
             const int p = tid / (LCS * H * 16), r2 = tid % (LCS * H * 16);
             int seg = p * spp + c * LCS + r2 / (H * 16);
             if (!EXACT) seg = seg < last_seg ? seg : last_seg;
-            stgs = *reinterpret_cast<const q_u32x4*>(sqt + (size_t)seg * (H * QSCL) + (r2 % (H * 16)) * 16);
+            const unsigned char* src = sqt;
+            if (DX) {
+                int pl_i, sg;
+                split(seg, pl_i, sg);
+                src += (size_t)pl_i * sq_plane;
+                seg = sg;
+            }
+            stgs = *reinterpret_cast<const q_u32x4*>(src + (size_t)seg * (H * QSCL) + (r2 % (H * 16)) * 16);
         }
     };
     auto stage_store = [&](int buf) {
@@ -734,6 +761,15 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) bits[slot][i][jj] = v4[jj];
             }
+            return;
+        }
+        if (DX) {  // plane and segment of the virtual segment (cw % 16 == 0: whole segments)
+            int pl_i, sg;
+            split(seg, pl_i, sg);
+            const q_u32x4 v4 = *reinterpret_cast<const q_u32x4*>(planes + (int64_t)pl_i * plane_stride +
+                                                                  (roff + (uint32_t)sg * 16u + 4u * (uint32_t)g));
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) bits[slot][0][jj] = v4[jj];
             return;
         }
         uint32_t w0 = (uint32_t)seg * 16u + 4u * (uint32_t)g;
@@ -1182,7 +1218,8 @@ template <int MODE, int QP, bool TWO, bool GROUPED, int KW, bool EXACT, bool TIL
 static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq, const unsigned char* sq,
                                  const float* alpha, const bf16_t* dy, void* out, int64_t T, int64_t rows, int64_t cw,
                                  int q_used, float scale, const LdsPlan& lp, int64_t segs, int tiles, int gsegs, int G,
-                                 hipStream_t st) {
+                                 hipStream_t st, int64_t xq_plane = 0, int64_t sq_plane = 0, uint32_t seg_magic = 0,
+                                 int segs_n = 0) {
     constexpr int H = TWO ? 2 : 1;
     constexpr int LDS_B = 2 * KW * LCS * H * (4 * QBLK + QSCL);
     static bool attr_set = false;
@@ -1193,8 +1230,30 @@ static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq
         attr_set = true;
     }
     hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
-                       LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G);
+                       LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G, xq_plane,
+                       sq_plane, seg_magic, segs_n);
     return hipGetLastError();
+}
+
+// input gradient through stream_lds_kernel: one virtual plane over q * segs_n segments
+static hipError_t launch_lds_dx(const uint32_t* twin, const unsigned char* xq, const unsigned char* sq, void* out, int64_t T,
+                                int64_t rows, int64_t cw, const LdsPlan& lp, int64_t vsegs, int tiles, int halves,
+                                int64_t xq_plane, int64_t sq_plane, int segs_n, hipStream_t st) {
+    const uint32_t magic = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)segs_n - 1) / (uint64_t)segs_n);
+#define BCQ_LDS_DX(TT, KW, EX)                                                                                          \
+    return launch_lds_cfg<STREAM_DX, 1, TT, false, KW, EX, false>(twin, xq, sq, nullptr, nullptr, out, T, rows, cw, 1, 1.f, lp, \
+                                                                  vsegs, tiles, 1, 1, st, xq_plane, sq_plane, magic, segs_n)
+    if (halves == 2) {
+        if (lp.exact) BCQ_LDS_DX(true, 1, true);
+        BCQ_LDS_DX(true, 1, false);
+    }
+    if (lp.KW == 2) {
+        if (lp.exact) BCQ_LDS_DX(false, 2, true);
+        BCQ_LDS_DX(false, 2, false);
+    }
+    if (lp.exact) BCQ_LDS_DX(false, 1, true);
+    BCQ_LDS_DX(false, 1, false);
+#undef BCQ_LDS_DX
 }
 
 template <int MODE, int QP, bool TWO, bool GROUPED, bool TILED>
@@ -1307,6 +1366,15 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
                            p.tiles, xq, sq, p.xq_bytes, p.sq_bytes, G);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+    }
+    if constexpr (MODE == STREAM_DX) {
+        if (G == 1 && cw % 16 == 0) {  // row-wise scales, whole segments
+            const int64_t vsegs = (int64_t)q_used * p.segs;
+            const LdsPlan lp = lds_plan(rows, vsegs, p.halves, 0, 1);
+            if (lp.KW > 0)
+                return launch_lds_dx(planes, xq, sq, out, T, rows, cw, lp, vsegs, p.tiles, p.halves, (int64_t)p.xq_bytes,
+                                     (int64_t)p.sq_bytes, (int)p.segs, st);
+        }
     }
     if constexpr (MODE != STREAM_DX) {
         if (TILED || cw % 4 == 0) {

@@ -177,6 +177,29 @@ def test_many_rows_streaming_parity(bcq, oracle, T, N, K, g, q):
     assert nmax_err(to_host(da).reshape(ref_da.shape), ref_da) <= tol
 
 
+MANY_COLUMNS = [
+    # input gradient of layers with many columns: the transposed twin is a plane matrix with many rows (K of them) and
+    # the workgroups share the re-coded, per-plane scaled activations through LDS; virtual segments = q * N / 512
+    # T, N, K, q
+    (8, 2048, 14336, 4),    # two parts of 8 virtual segments (planes 0-1 / 2-3): guard-free instantiation
+    (5, 3072, 14368, 3),    # ragged rows; 18 virtual segments in parts of 9 that straddle the planes: guarded
+    (12, 2048, 28672, 4),   # two register halves per token tile: one part, 8 row tiles
+    (40, 2048, 28672, 2),   # three token tiles (grid y), the last one ragged
+    (8, 1024, 14336, 4),    # too few segments for the shared form: per-wave kernel
+]
+
+
+@pytest.mark.parametrize("T,N,K,q", MANY_COLUMNS)
+def test_many_columns_input_gradient_streaming(bcq, oracle, T, N, K, q):
+    W, alpha, planes, packed, x, dy = make_case(3, "mlp_down", T, N, K, q, "bf16", oracle)
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha[:, :, None])
+    d_twin = bcq.bcq_pack_transposed(d_packed)
+    dx = bcq.bcq_linear_bwd_input_grouped(d_packed, d_alpha, to_dev(dy, "bf16"), K, packed_t=d_twin,
+                                          workspace=_ws(bcq, 2, T, N, K, K, q, 1))
+    _sync()
+    assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol_for("bf16")
+
+
 def test_many_rows_two_token_tiles_and_partial_training(bcq, oracle):
     """17 .. 31 tokens are two token tiles of the forward (grid y); the scale gradient of the first planes only."""
     T, N, K, q = 20, 28672, 4096, 2
