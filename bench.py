@@ -31,7 +31,7 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3  # 256 compute units x 4 SIMDs x 16 lanes x 2 fl
 PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.76e7, (2, 4096, 4, "bwd_input"): 7.76e7}
 # the same for one whole step of `--config 5 --layer 16384x16384 --tokens 8` per layer copy (fwd 141.2 MB, dalpha 138.6 MB,
 # dx 154.5 MB, the three activation pre-kernels 2.8 MB; profiles/stream_large_layer_kernel_stats.md)
-PMC_TRAFFIC_STREAM_LAYER = {((16384, 16384), 8, 4): 4.370e8}
+PMC_TRAFFIC_STREAM_LAYER = {((16384, 16384), 8, 4): 4.252e8}
 
 
 def parse():
