@@ -619,9 +619,10 @@ __device__ __forceinline__ void stream_finish(q_f32x4 (&acc)[QP], float (&ep)[QP
 // ring of LCS register sets addressed by the unrolled position, LCS - 1 segments ahead of the multiplication (a
 // register move would have to wait for the load it copies).  Needs cw % 4 == 0.
 // EXACT: every part has spp segments and spp % LCS == 0 - no guards in the loop.
-// Input gradient (STREAM_DX, row-wise scales): every plane has its own scaled activations, so nothing of the operand
-// is shared between planes and the call is a one-plane forward over q * segs_n VIRTUAL segments of the transposed
-// twin: virtual segment v = plane v / segs_n, segment v % segs_n (the division is a multiplication by seg_magic).
+// Input gradient (STREAM_DX): every plane (and, with group-wise scales, every scale group of the workgroup's rows) has
+// its own scaled activations, so nothing of the operand is shared between planes and the call is a one-plane forward
+// over q * segs_n VIRTUAL segments of the transposed twin: virtual segment v = plane v / segs_n, segment v % segs_n
+// (the division is a multiplication by seg_magic).
 constexpr int LCS = 4;
 
 // 32 signs of a packed word -> the four FP4 operand registers of a lane (+1 = 0x2, -1 = 0xA; registers 4 .. 7 of the
@@ -645,7 +646,7 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
                                                           int spp, int64_t segs, int gsegs, int G, int64_t xq_plane,
                                                           int64_t sq_plane, uint32_t seg_magic, int segs_n) {
     constexpr bool DX = (MODE == STREAM_DX);
-    static_assert(!DX || (QP == 1 && !GROUPED && !TILED), "input gradient: one virtual plane, row-wise scales, twin layout");
+    static_assert(!DX || (QP == 1 && !GROUPED && !TILED), "input gradient: one virtual plane, twin layout (scale groups are handled at run time)");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int H = TWO ? 2 : 1, RW = 8 / KW, PF = LCS - 1;
     constexpr int XPART = LCS * 4 * H * QBLK, XBUF = KW * XPART;  // operand blocks of one part / of one buffer
@@ -703,6 +704,9 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
         pl_i = (int)(((uint64_t)(uint32_t)vseg * seg_magic) >> 32);
         sg = vseg - pl_i * segs_n;
     };
+    // DX with group-wise scales: G activation sets per plane; the rows of a workgroup (at most 128, g % 512 == 0) lie
+    // in one scale group
+    const int dx_grp = (DX && G > 1) ? (int)(((int64_t)blockIdx.x * RW * 16) / (rows / G)) : 0;
     const int part_begin = kp * spp;
     int part_end = part_begin + spp;
     part_end = part_end < (int)segs ? part_end : (int)segs;
@@ -722,7 +726,7 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
             if (DX) {
                 int pl_i, sg;
                 split(seg, pl_i, sg);
-                src += (size_t)pl_i * xq_plane;
+                src += (size_t)(pl_i * G + dx_grp) * xq_plane;
                 seg = sg;
             }
             stg[it] = *reinterpret_cast<const q_u32x4*>(src + (size_t)seg * (4 * H * QBLK) + (r % H) * 8192 + tid * 16);
@@ -735,7 +739,7 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
             if (DX) {
                 int pl_i, sg;
                 split(seg, pl_i, sg);
-                src += (size_t)pl_i * sq_plane;
+                src += (size_t)(pl_i * G + dx_grp) * sq_plane;
                 seg = sg;
             }
             stgs = *reinterpret_cast<const q_u32x4*>(src + (size_t)seg * (H * QSCL) + (r2 % (H * 16)) * 16);
@@ -1238,11 +1242,11 @@ static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq
 // input gradient through stream_lds_kernel: one virtual plane over q * segs_n segments
 static hipError_t launch_lds_dx(const uint32_t* twin, const unsigned char* xq, const unsigned char* sq, void* out, int64_t T,
                                 int64_t rows, int64_t cw, const LdsPlan& lp, int64_t vsegs, int tiles, int halves,
-                                int64_t xq_plane, int64_t sq_plane, int segs_n, hipStream_t st) {
+                                int64_t xq_plane, int64_t sq_plane, int segs_n, int G, hipStream_t st) {
     const uint32_t magic = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)segs_n - 1) / (uint64_t)segs_n);
 #define BCQ_LDS_DX(TT, KW, EX)                                                                                          \
     return launch_lds_cfg<STREAM_DX, 1, TT, false, KW, EX, false>(twin, xq, sq, nullptr, nullptr, out, T, rows, cw, 1, 1.f, lp, \
-                                                                  vsegs, tiles, 1, 1, st, xq_plane, sq_plane, magic, segs_n)
+                                                                  vsegs, tiles, 1, G, st, xq_plane, sq_plane, magic, segs_n)
     if (halves == 2) {
         if (lp.exact) BCQ_LDS_DX(true, 1, true);
         BCQ_LDS_DX(true, 1, false);
@@ -1368,12 +1372,12 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
         if (e != hipSuccess) return e;
     }
     if constexpr (MODE == STREAM_DX) {
-        if (G == 1 && cw % 16 == 0) {  // row-wise scales, whole segments
+        if (cw % 16 == 0) {  // whole segments
             const int64_t vsegs = (int64_t)q_used * p.segs;
             const LdsPlan lp = lds_plan(rows, vsegs, p.halves, 0, 1);
             if (lp.KW > 0)
                 return launch_lds_dx(planes, xq, sq, out, T, rows, cw, lp, vsegs, p.tiles, p.halves, (int64_t)p.xq_bytes,
-                                     (int64_t)p.sq_bytes, (int)p.segs, st);
+                                     (int64_t)p.sq_bytes, (int)p.segs, G, st);
         }
     }
     if constexpr (MODE != STREAM_DX) {

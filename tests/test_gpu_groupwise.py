@@ -200,6 +200,19 @@ def test_many_columns_input_gradient_streaming(bcq, oracle, T, N, K, q):
     assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol_for("bf16")
 
 
+@pytest.mark.parametrize("T,N,K,g,q", [(8, 2048, 14336, 1024, 4), (12, 2048, 28672, 512, 3)])
+def test_many_columns_input_gradient_streaming_groupwise(bcq, oracle, T, N, K, g, q):
+    """Group-wise scales: one set of scaled activations per plane and scale group; a workgroup's rows of the twin lie
+    in one group."""
+    W, alpha, planes, packed, x, dy = make_case(3, "mlp_down", T, N, K, q, "bf16", oracle, g=g)
+    d_packed, d_alpha = packed_to_dev(packed), to_dev(alpha)
+    d_twin = bcq.bcq_pack_transposed(d_packed)
+    dx = bcq.bcq_linear_bwd_input_grouped(d_packed, d_alpha, to_dev(dy, "bf16"), g, packed_t=d_twin,
+                                          workspace=_ws(bcq, 2, T, N, K, g, q, 1))
+    _sync()
+    assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol_for("bf16")  # alpha is [q][N][K / g]
+
+
 def test_many_rows_two_token_tiles_and_partial_training(bcq, oracle):
     """17 .. 31 tokens are two token tiles of the forward (grid y); the scale gradient of the first planes only."""
     T, N, K, q = 20, 28672, 4096, 2
