@@ -77,6 +77,48 @@ def _sampled_layer(bcq, oracle, config, kind, T, q, dtype, outliers=False, full=
     return errs
 
 
+@pytest.mark.parametrize("T,N,K", [
+    (4000, 4040, 160),    # forward: 16 x 16 tiles of 256 x 256, ragged in T and N, last K-step beyond K
+    (4000, 160, 4032),    # the same for the input gradient (256 x 256 tiles over T x K, contraction N = 160)
+    (2000, 3000, 1056),   # forward: 128 x 128 tiles, ragged in T and N, K / 32 odd
+])
+def test_large_tiles_ragged_edges(bcq, oracle, T, N, K):
+    """The workloads' shapes are multiples of 256, so the large tiles of the matrix-core kernels see ragged token rows,
+    ragged output columns and a contraction that ends inside a K-step only here.  Sampled outputs (random entries, the
+    last token rows and the last output columns in full) against the oracle; scale gradient on sampled rows incl. the
+    last ones."""
+    import torch
+    q = 3
+    W = synth.weights(4, "out", N, K)
+    a_ref, b_ref, alpha, packed = _quantize_and_check(bcq, oracle, W, q)
+    x = synth.activations(4, "out", T, K, 1, "bf16")
+    dy = synth.activations(4, "out", T, N, 2, "bf16")
+    d_x, d_dy = to_dev(x, "bf16"), to_dev(dy, "bf16")
+    twin = bcq.bcq_pack_transposed(packed) if N % 32 == 0 else None
+    y = bcq.bcq_linear_fwd(packed, alpha, d_x, workspace=_ws(bcq, 1, T, N, K, q, 1))
+    dx = bcq.bcq_linear_bwd_input(packed, alpha, d_dy, packed_t=twin, workspace=_ws(bcq, 2, T, N, K, q, 1))
+    da = bcq.bcq_linear_bwd_alpha(packed, d_x, d_dy, workspace=_ws(bcq, 3, T, N, K, q, 1))
+    torch.cuda.synchronize()
+    y, dx, da = to_host(y), to_host(dx), to_host(da)
+    tol = tol_for("bf16")
+
+    def samples(seed, rows, cols):
+        tt, cc = synth.sample_indices(seed, rows, cols, 2048)
+        last_r = np.repeat(np.arange(rows - 2, rows), min(cols, 512))           # the last two token rows
+        last_r_c = np.tile(np.arange(cols - min(cols, 512), cols), 2)
+        last_c = np.tile(np.arange(cols - 2, cols), min(rows, 512))             # the last two columns
+        last_c_r = np.repeat(np.arange(rows - min(rows, 512), rows), 2)
+        return (np.concatenate([tt, last_r, last_c_r]).astype(np.int64),
+                np.concatenate([cc, last_r_c, last_c]).astype(np.int64))
+
+    tt, nn = samples(41, T, N)
+    assert nmax_err(y[tt, nn], oracle.fwd_at(a_ref, b_ref, x, tt, nn)) <= tol
+    tt, kk = samples(42, T, K)
+    assert nmax_err(dx[tt, kk], oracle.bwd_input_at(a_ref, b_ref, dy, tt, kk)) <= tol
+    rows = np.concatenate([np.random.default_rng(43).choice(N - 8, size=24, replace=False), np.arange(N - 8, N)])
+    assert nmax_err(da[:, rows], oracle.bwd_alpha_rows(b_ref, x, dy, rows)) <= tol
+
+
 @pytest.mark.parametrize("kind", synth.LAYER_KINDS)
 def test_config2_gpt2_medium_block(bcq, oracle, kind):
     """d = 1024, q = 4, bf16, T = 8 x 512: the workload bench.py times."""
