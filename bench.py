@@ -55,8 +55,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="skip the per-op HIP events (pure step timing)")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="keep the whole step on one stream.  By default (32 tokens and more) the scale gradients run on "
-                         "a second HIP stream of default priority, joined at the end of the step: in training dalpha "
+                    help="keep the whole step on one stream.  By default (32 tokens and more) a step is ordered like a "
+                         "training step (all forwards, then the backward pass from the last layer) and the scale gradients "
+                         "run on a second HIP stream of default priority beside the input gradients, joined at the end "
+                         "of the step: in training dalpha "
                          "is a leaf of the backward pass (Eq. 4), only the optimizer waits for it")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every timed step from Python instead of replaying one captured HIP graph (a step is 32 "
@@ -157,11 +159,14 @@ def main():
     side = torch.cuda.Stream() if (not args.no_overlap and not small) else None
 
     def step_overlapped():
-        """fwd and dx of every layer on the current stream, dalpha on the side stream; one join at the end."""
+        """Ordered like a training step: the forward of every layer first; then, from the last layer back, the input
+        gradient on the current stream and the scale gradient on the side stream (it is a leaf of the backward pass:
+        only the optimizer waits for it); one join at the end."""
         main = torch.cuda.current_stream()
-        side.wait_stream(main)
         for L in layers:
             run_op(L, "fwd")
+        side.wait_stream(main)  # the backward pass starts when the forward is done
+        for L in reversed(layers):
             with torch.cuda.stream(side):
                 run_op(L, "bwd_alpha")
             run_op(L, "bwd_input")
