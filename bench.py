@@ -382,7 +382,9 @@ def main():
                                                   ("g=%d group-wise" % args.g) if args.g else "row-wise", dtype, T),
                    "h": h, "q": q, "tokens": T, "g": args.g or "h_in", "weights_per_block": weights_total // replicas,
                    "layer_stack_replicas": replicas, "hip_graph": graph is not None,
-                   "streams": 2 if side is not None else 1},
+                   "streams": 2 if side is not None else 1,
+                   "order": ("training step: all forwards, then from the last layer back dx on the main stream and "
+                             "dalpha on the second stream, one join") if side is not None else "fwd, dx, dalpha per layer"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "context": context,
