@@ -189,13 +189,9 @@ hipError_t launch_quantize_alternating(const float* W, int64_t V, int64_t n, int
         if (e != hipSuccess) return e;
     }
     const size_t lds = (size_t)(4 * ALT_NRED + 256) * sizeof(double) + (size_t)n * 5;
-    static size_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        hipError_t ea = hipFuncSetAttribute((const void*)alternating_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)lds);
-        if (ea != hipSuccess) return ea;
-        lds_allowed = lds;
-    }
+    static LdsLimit limit;
+    hipError_t ea = limit.ensure((const void*)alternating_kernel, lds);
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL(alternating_kernel, dim3((unsigned)V), dim3(ALT_THREADS), lds, st, W, V, (int)n, q, iters, alpha,
                        packed, planes, status_word);
     return hipGetLastError();

@@ -51,6 +51,25 @@ __device__ __forceinline__ void adamw_apply(const AdamWArgs& o, int64_t idx, flo
 // alpha, m, v <- AdamW(alpha, dalpha) over `count` scales
 hipError_t launch_adamw(const float* dalpha, int64_t count, AdamWArgs args, hipStream_t st);
 
+// The dynamic-LDS limit of a kernel is a property of (kernel, device).  One instance per kernel remembers, for every
+// device of the process, the largest size already allowed there (64 KiB are allowed without asking).  Racing first
+// calls from several host threads set the same attribute twice, which is harmless.
+struct LdsLimit {
+    size_t allowed[64] = {};
+    hipError_t ensure(const void* kernel, size_t bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        const size_t have = allowed[dev] > (size_t)(64 * 1024) ? allowed[dev] : (size_t)(64 * 1024);
+        if (bytes <= have) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        allowed[dev] = bytes;
+        return hipSuccess;
+    }
+};
+
 // ---- one-time kernels -----------------------------------------------------------------------
 hipError_t launch_pack(const int8_t* planes, int64_t total_words, uint32_t* packed, hipStream_t st);
 hipError_t launch_unpack(const uint32_t* packed, int64_t total_words, int8_t* planes, hipStream_t st);

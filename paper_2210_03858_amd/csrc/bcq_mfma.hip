@@ -479,13 +479,9 @@ template <int TM, int TN>
 static hipError_t launch_gemm_cfg(const bf16_t* A, int64_t lda, const u32x4* frag, bf16_t* C, int64_t ldc, int64_t M,
                                   int64_t NC, int64_t R, int64_t R16, hipStream_t st) {
     using Cfg = GemmCfg<TM, TN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<TM, TN>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_B);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure((const void*)gemm_kernel<TM, TN>, Cfg::LDS_B);
+    if (e != hipSuccess) return e;
     const int tiles_m = (int)((M + Cfg::BMT - 1) / Cfg::BMT), tiles_n = (int)((NC + Cfg::BNT - 1) / Cfg::BNT);
     TileMap tmap;
     const unsigned wgs = make_tile_map(tiles_m, tiles_n, 1, 32 * Cfg::OCC, (double)Cfg::BMT, (double)Cfg::BNT, &tmap);
@@ -979,13 +975,9 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     const int qt = q_train <= 4 ? q_train : 8;
 #define BCQ_DA_LAUNCH(XGV, QTV, FV)                                                                                   \
     {                                                                                                                 \
-        static bool attr_set = false;                                                                                 \
-        if (!attr_set) {                                                                                              \
-            hipError_t ea = hipFuncSetAttribute((const void*)dalpha_kernel<XGV, QTV, FV>,                              \
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);                     \
-            if (ea != hipSuccess) return ea;                                                                          \
-            attr_set = true;                                                                                          \
-        }                                                                                                             \
+        static LdsLimit limit;                                                                                        \
+        hipError_t ea = limit.ensure((const void*)dalpha_kernel<XGV, QTV, FV>, (size_t)lds);                           \
+        if (ea != hipSuccess) return ea;                                                                              \
         hipLaunchKernelGGL((dalpha_kernel<XGV, QTV, FV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16,  \
                            packed, part, T, N, K, q_train, tmap, pl.splits, pl.per_split);                            \
     }

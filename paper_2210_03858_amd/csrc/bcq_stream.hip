@@ -1226,13 +1226,9 @@ static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq
                                  int segs_n = 0) {
     constexpr int H = TWO ? 2 : 1;
     constexpr int LDS_B = 2 * KW * LCS * H * (4 * QBLK + QSCL);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_B);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>, LDS_B);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
                        LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G, xq_plane,
                        sq_plane, seg_magic, segs_n);
@@ -1316,13 +1312,9 @@ static hipError_t launch_fused_cfg(const uint32_t* planes, const bf16_t* act, co
     const int nout = (MODE == STREAM_DALPHA) ? q_used : 1;
     const size_t stage = (size_t)p.W * (4 * H * QBLK + H * QSCL), red = (size_t)p.W * nout * 1024;
     const size_t lds = stage > red ? stage : red;
-    static size_t lds_allowed = 64 * 1024;
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute((const void*)stream_fused_kernel<MODE, QP, TWO>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    static LdsLimit limit;
+    hipError_t e = limit.ensure((const void*)stream_fused_kernel<MODE, QP, TWO>, lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((stream_fused_kernel<MODE, QP, TWO>), dim3(p.grid_x, (unsigned)p.tiles), dim3((unsigned)(64 * p.W)),
                        lds, st, planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, gsegs, G);
     return hipGetLastError();
