@@ -186,6 +186,7 @@ MANY_COLUMNS = [
     (12, 2048, 28672, 4),   # two register halves per token tile: one part, 8 row tiles
     (40, 2048, 28672, 2),   # three token tiles (grid y), the last one ragged
     (8, 1024, 14336, 4),    # too few segments for the shared form: per-wave kernel
+    (7, 2560, 10240, 4),    # 160 workgroups: the smallest twin that takes the shared form (20 virtual segments, guarded)
 ]
 
 
