@@ -1369,7 +1369,7 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
             // the per-wave kernel fetches one activation set per plane and row tile, so sharing pays from fewer
             // workgroups than for the forward (measured at 8 tokens: 10240 rows 18.0 -> 14.9 us, 12288 rows equal,
             // 6144 rows 3 % slower)
-            const LdsPlan lp = lds_plan(rows, vsegs, p.halves, 0, 1, 160);
+            const LdsPlan lp = lds_plan(rows, vsegs, p.halves, 0, 1, p.halves == 1 ? 160 : 224);
             if (lp.KW > 0)
                 return launch_lds_dx(planes, xq, sq, out, T, rows, cw, lp, vsegs, p.tiles, p.halves, (int64_t)p.xq_bytes,
                                      (int64_t)p.sq_bytes, (int)p.segs, G, st);
