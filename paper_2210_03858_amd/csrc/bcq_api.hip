@@ -6,20 +6,37 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
+// One capability probe per device, cached: 0 = unknown, 1 = gfx950, 2 = anything else.  Racing first calls store
+// the same value.
+bool bcq::host::device_ok() {
+    static std::atomic<int> cache[64];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return false;
+    }
+    int c = cache[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        c = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+        cache[dev].store(c, std::memory_order_relaxed);
+    }
+    return c == 1;
+}
+
 namespace {
 
-constexpr int64_t kMaxDim = (int64_t)1 << 17;      // N, K
-constexpr int64_t kMaxTokens = (int64_t)1 << 24;   // T
-constexpr int64_t kMaxElems = (int64_t)1 << 40;    // N*K, T*N, T*K
-
-inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+using bcq::host::kMaxElems;
+using bcq::host::misaligned;
 
 bcq_status check_shape(int64_t T, int64_t N, int64_t K, int q) {
-    if (N < 1 || K < 1 || T < 1 || q < 1 || q > 8) return BCQ_ERR_SHAPE;
-    if (K % 32 != 0) return BCQ_ERR_SHAPE;
-    if (N > kMaxDim || K > kMaxDim || T > kMaxTokens) return BCQ_ERR_SHAPE;
-    if (N * K > kMaxElems || T * N > kMaxElems || T * K > kMaxElems) return BCQ_ERR_SHAPE;
-    return BCQ_OK;
+    return bcq::host::shape_ok(T, N, K, q) ? BCQ_OK : BCQ_ERR_SHAPE;
 }
 
 // Group size along K: a multiple of 32 (a packed word never straddles two groups) that divides K.
@@ -28,24 +45,7 @@ bcq_status check_group(int64_t K, int64_t g) {
     return BCQ_OK;
 }
 
-// One capability probe per device, cached: 1 = gfx950, 0 = anything else.
-bcq_status check_device() {
-    static int cache[64];  // 0 = unknown, 1 = ok, 2 = wrong
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
-        (void)hipGetLastError();
-        return BCQ_ERR_DEVICE;
-    }
-    if (cache[dev] == 0) {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
-            (void)hipGetLastError();
-            return BCQ_ERR_DEVICE;
-        }
-        cache[dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
-    }
-    return cache[dev] == 1 ? BCQ_OK : BCQ_ERR_DEVICE;
-}
+bcq_status check_device() { return bcq::host::device_ok() ? BCQ_OK : BCQ_ERR_DEVICE; }
 
 inline bcq_status done(hipError_t e) { return e == hipSuccess ? BCQ_OK : BCQ_ERR_DEVICE; }
 
@@ -133,7 +133,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 5; }
+int bcq_abi_version(void) { return 6; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {

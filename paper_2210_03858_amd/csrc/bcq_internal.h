@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace bcq {
 
 // ---- element helpers shared by all kernels -------------------------------------------------
@@ -53,22 +55,38 @@ hipError_t launch_adamw(const float* dalpha, int64_t count, AdamWArgs args, hipS
 
 // The dynamic-LDS limit of a kernel is a property of (kernel, device).  One instance per kernel remembers, for every
 // device of the process, the largest size already allowed there (64 KiB are allowed without asking).  Racing first
-// calls from several host threads set the same attribute twice, which is harmless.
+// calls from several host threads set the same attribute twice, which is harmless; the record itself is atomic.
 struct LdsLimit {
-    size_t allowed[64] = {};
+    std::atomic<size_t> allowed[64] = {};
     hipError_t ensure(const void* kernel, size_t bytes) {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        const size_t have = allowed[dev] > (size_t)(64 * 1024) ? allowed[dev] : (size_t)(64 * 1024);
+        const size_t seen = allowed[dev].load(std::memory_order_relaxed);
+        const size_t have = seen > (size_t)(64 * 1024) ? seen : (size_t)(64 * 1024);
         if (bytes <= have) return hipSuccess;
         e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
         if (e != hipSuccess) return e;
-        allowed[dev] = bytes;
+        allowed[dev].store(bytes, std::memory_order_relaxed);
         return hipSuccess;
     }
 };
+
+// ---- host-side argument checks shared by the source files that hold C-ABI entry points ------------------
+namespace host {
+constexpr int64_t kMaxDim = (int64_t)1 << 17;     // N, K
+constexpr int64_t kMaxTokens = (int64_t)1 << 24;  // T
+constexpr int64_t kMaxElems = (int64_t)1 << 40;   // N*K, T*N, T*K
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline bool shape_ok(int64_t T, int64_t N, int64_t K, int q) {
+    if (N < 1 || K < 1 || T < 1 || q < 1 || q > 8 || K % 32 != 0) return false;
+    if (N > kMaxDim || K > kMaxDim || T > kMaxTokens) return false;
+    return N * K <= kMaxElems && T * N <= kMaxElems && T * K <= kMaxElems;
+}
+// true when the calling thread's current device is a gfx950 (one probe per device, cached; thread-safe)
+bool device_ok();
+}  // namespace host
 
 // ---- one-time kernels -----------------------------------------------------------------------
 hipError_t launch_pack(const int8_t* planes, int64_t total_words, uint32_t* packed, hipStream_t st);

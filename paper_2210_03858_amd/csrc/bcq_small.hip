@@ -313,9 +313,15 @@ static hipError_t launch_small(const uint32_t* planes, const bf16_t* act, const 
     const int nout = (MODE == SMALL_DALPHA) ? q_used : 1;
     const size_t lds = (size_t)p.W * p.R * nout * 64 * 4 * sizeof(float);
     const int qp = q_used <= 4 ? q_used : 8;
+    // more than 64 KiB of dynamic LDS (many rows, 5 .. 8 trained planes) needs the kernel's limit raised first
 #define BCQ_SMALL_LAUNCH(RR, QQ)                                                                                   \
-    hipLaunchKernelGGL((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
-                       q_used, scale, p.segs_per_wave)
+    {                                                                                                              \
+        static LdsLimit limit;                                                                                     \
+        const hipError_t le = limit.ensure((const void*)small_kernel<MODE, RR, QQ>, lds);                          \
+        if (le != hipSuccess) return le;                                                                           \
+        hipLaunchKernelGGL((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
+                           q_used, scale, p.segs_per_wave);                                                        \
+    }
 #define BCQ_SMALL_Q(RR)                                          \
     switch (qp) {                                                \
         case 1: BCQ_SMALL_LAUNCH(RR, 1); break;                  \

@@ -704,8 +704,8 @@ __global__ __launch_bounds__(512) void stream_lds_kernel(const uint32_t* __restr
         pl_i = (int)(((uint64_t)(uint32_t)vseg * seg_magic) >> 32);
         sg = vseg - pl_i * segs_n;
     };
-    // DX with group-wise scales: G activation sets per plane; the rows of a workgroup (at most 128, g % 512 == 0) lie
-    // in one scale group
+    // DX with group-wise scales: G activation sets per plane; the host takes this kernel only when the rows of a
+    // workgroup (16 RW of them) lie in one scale group
     const int dx_grp = (DX && G > 1) ? (int)(((int64_t)blockIdx.x * RW * 16) / (rows / G)) : 0;
     const int part_begin = kp * spp;
     int part_end = part_begin + spp;
@@ -1370,7 +1370,10 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
             // workgroups than for the forward (measured at 8 tokens: 10240 rows 18.0 -> 14.9 us, 12288 rows equal,
             // 6144 rows 3 % slower)
             const LdsPlan lp = lds_plan(rows, vsegs, p.halves, 0, 1, p.halves == 1 ? 160 : 224);
-            if (lp.KW > 0)
+            // group-wise scales: a workgroup (8 / KW row tiles of the twin) takes ONE activation set, so its rows must
+            // lie in one scale group; other group sizes keep the per-wave kernel (16 rows per workgroup, g % 32 == 0)
+            const bool one_group = (G == 1) || (lp.KW > 0 && g % (16 * (8 / lp.KW)) == 0);
+            if (lp.KW > 0 && one_group)
                 return launch_lds_dx(planes, xq, sq, out, T, rows, cw, lp, vsegs, p.tiles, p.halves, (int64_t)p.xq_bytes,
                                      (int64_t)p.sq_bytes, (int)p.segs, G, st);
         }

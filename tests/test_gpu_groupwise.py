@@ -201,7 +201,11 @@ def test_many_columns_input_gradient_streaming(bcq, oracle, T, N, K, q):
     assert nmax_err(to_host(dx), oracle.bwd_input(alpha, planes, dy)) <= tol_for("bf16")
 
 
-@pytest.mark.parametrize("T,N,K,g,q", [(8, 2048, 14336, 1024, 4), (12, 2048, 28672, 512, 3)])
+@pytest.mark.parametrize("T,N,K,g,q", [(8, 2048, 14336, 1024, 4), (12, 2048, 28672, 512, 3),
+                                       # groups of 160 columns: a shared-activation workgroup (64 or 128 rows of the twin)
+                                       # would straddle two groups, so these must take the per-wave kernel
+                                       (8, 2560, 10240, 160, 4), (8, 2560, 20480, 160, 2),
+                                       (8, 2560, 10240, 128, 2)])  # 128-row workgroups inside 128-column groups
 def test_many_columns_input_gradient_streaming_groupwise(bcq, oracle, T, N, K, g, q):
     """Group-wise scales: one set of scaled activations per plane and scale group; a workgroup's rows of the twin lie
     in one group."""

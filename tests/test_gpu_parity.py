@@ -175,6 +175,12 @@ def test_few_hundred_tokens_small_gemm_tiles(bcq, oracle, T, N, K, q):
     _run_layer(bcq, oracle, 3, "mlp_up", T, N, K, q, "bf16", workspace=True, twin=(N % 32 == 0))
 
 
+def test_many_rows_eight_planes_without_workspace(bcq, oracle):
+    """16384 rows and more put two row tiles into a wave of the workspace-free small-token kernel; with 5 .. 8 trained
+    planes its cross-wave sum then needs more than 64 KiB of LDS, which the launcher must ask for."""
+    _run_layer(bcq, oracle, 3, "mlp_up", 3, 16400, 4096, 8, "bf16", workspace=False, twin=False)
+
+
 @pytest.mark.parametrize("T,N,K", [(100, 96, 96), (130, 160, 224), (257, 64, 32)])
 def test_nonfinite_token_row_stays_in_its_row(bcq, oracle, T, N, K):
     """Tiled kernels pad the contraction to a multiple of 128 and the token tile to 64 or more rows: what they read
