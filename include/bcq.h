@@ -81,7 +81,7 @@ typedef enum {
 const char* bcq_status_string(bcq_status s);
 
 /* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points;
- * 5: decode layout). */
+ * 5: decode layout; 6: bcq_linear_fwd_static). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -164,6 +164,27 @@ bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, cons
 bcq_status bcq_linear_fwd(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
                           int64_t N, int64_t K, int q, void* y, void* workspace, size_t workspace_bytes,
                           void* stream);
+
+/* bcq_linear_fwd for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as bcq_linear_fwd with a workspace
+ * (row-wise scales, bf16 activations, at most BCQ_STATIC_MAX_TOKENS tokens: the streaming kernels), but the scratch
+ * of those kernels - the activations re-coded as two block-scaled FP8 terms - lives in a fixed array of
+ * BCQ_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing and calls no allocating routine.
+ *   packed [q][N][K/32] in; alpha [q][N] fp32 in; x [T][K] bf16 in; y [T][N] bf16 out (caller-owned, as everywhere).
+ * Errors: BCQ_ERR_DTYPE unless dtype == BCQ_BF16; BCQ_ERR_SHAPE for T > BCQ_STATIC_MAX_TOKENS (and the usual shape
+ * limits); BCQ_ERR_WORKSPACE when the re-coded activations do not fit the array, i.e. when
+ * bcq_workspace_bytes(BCQ_OP_FWD, T, N, K, q, BCQ_BF16) > BCQ_STATIC_SCRATCH_BYTES (about 1056 bytes per token rounded
+ * up to 8 or a multiple of 16, per 512 columns of K: T <= 8 fits any K <= 2^17 - 4096, T <= 16 K <= 63488, T <= 80 K <= 12288);
+ * the others as for bcq_linear_fwd.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different streams or
+ * host threads) race on it and give unspecified results; calls on one stream, or ordered by events, are safe.  The
+ * array keeps the previous call's contents; every byte a call reads is written by that call first.
+ * The first call on a device looks the array's address up (a host-side query): make it before a graph capture. */
+#define BCQ_STATIC_SCRATCH_BYTES (2 * 1024 * 1024)
+#define BCQ_STATIC_MAX_TOKENS 80
+bcq_status bcq_linear_fwd_static(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                                 int64_t N, int64_t K, int q, void* y, void* stream);
 
 /* Eq. 2 with group-wise scales alpha [q][N][K/g]: y[t][n] = sum_k x[t][k] * sum_i alpha_i[n][k/g] * B_i[n][k]. */
 bcq_status bcq_linear_fwd_grouped(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,

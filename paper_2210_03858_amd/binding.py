@@ -22,7 +22,7 @@ EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_q
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
            "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
            "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw", "bcq_decode_layout_bytes", "bcq_pack_decode",
-           "bcq_linear_fwd_decode")
+           "bcq_linear_fwd_decode", "bcq_linear_fwd_static")
 
 _lib = None
 
@@ -73,6 +73,7 @@ def load():
     lib.bcq_decode_layout_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(sz)]
     lib.bcq_pack_decode.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.bcq_linear_fwd_decode.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
+    lib.bcq_linear_fwd_static.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -236,6 +237,26 @@ def bcq_linear_fwd(packed, alpha, x, y=None, workspace=None):
     wp, wb = _ws(workspace)
     _check(load().bcq_linear_fwd(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, q, _ptr(y), wp, wb, _stream()),
            "bcq_linear_fwd")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
+STATIC_MAX_TOKENS = 80
+
+
+def bcq_linear_fwd_static(packed, alpha, x, y):
+    """Small-token forward into the caller's y, scratch in the library's static device array: no allocation anywhere
+    (y is required for that reason)."""
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    dt = _act_dtype(x)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N), "alpha")
+    _need(x, x.dtype, (T, K), "x")
+    _need(y, x.dtype, (T, N), "y")
+    _check(load().bcq_linear_fwd_static(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, q, _ptr(y), _stream()),
+           "bcq_linear_fwd_static")
     return y
 
 

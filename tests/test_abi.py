@@ -130,6 +130,20 @@ def test_decode_layout_errors_before_device(lib):
     assert lib.bcq_linear_fwd_decode(A, A, A + 2, 1, T, N, K, i64(K), q, A, A, ws, None) == 4
 
 
+def test_fwd_static_errors_before_device(lib):
+    q, N, K, T = 3, 64, 1024, 8
+    assert lib.bcq_linear_fwd_static(A, A, A, 1, T, N, K, q, None, None) == 1
+    assert lib.bcq_linear_fwd_static(A, A, A, 1, 81, N, K, q, A, None) == 2       # at most 80 tokens
+    assert lib.bcq_linear_fwd_static(A, A, A, 1, T, N, 1000, q, A, None) == 2
+    assert lib.bcq_linear_fwd_static(A, A, A, 0, T, N, K, q, A, None) == 3        # bf16 only
+    assert lib.bcq_linear_fwd_static(A, A + 8, A, 1, T, N, K, q, A, None) == 4
+    assert lib.bcq_linear_fwd_static(A, A, A, 1, 80, N, 12800, q, A, None) == 5   # 2112000 bytes of scratch > 2 MiB
+    assert lib.bcq_linear_fwd_static(A, A, A, 1, 16, N, 63488 + 512, q, A, None) == 5
+    import torch
+    if not torch.cuda.is_available():
+        assert lib.bcq_linear_fwd_static(A, A, A, 1, 80, N, 12288, q, A, None) == 7  # fits; no device here
+
+
 def test_no_device_is_reported(lib):
     import torch
     if torch.cuda.is_available():
