@@ -81,7 +81,8 @@ typedef enum {
 const char* bcq_status_string(bcq_status s);
 
 /* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points;
- * 5: decode layout; 6: bcq_linear_fwd_static). */
+ * 5: decode layout; 6: bcq_linear_fwd_static;
+ * 7: batched small-token calls). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -220,6 +221,59 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
 bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, const void* dy, int dtype, int64_t T,
                                         int64_t N, int64_t K, int64_t g, int q, int q_train, float grad_scale,
                                         float* dalpha, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Batched small-token calls: many independent layers in two launches ------------------------------------------
+ * Section 3 notes that small-batch inference is memory-bound and Section 6 ("Inference Speed") expects a latency gain
+ * in proportion to the memory reduction.  A single layer of the paper's models holds only 0.2 - 13 MB of sign planes
+ * (Table 1), less than a microsecond of HBM time, so a call per layer is bound by launches.  These entry points run
+ * ONE operation - forward (Eq. 2), input gradient (Eq. 3) or scale gradient (Eq. 4) - for `count` layers at once:
+ * one activation re-coding launch and one streaming launch whose workgroups look their layer up in a plan.
+ * The layers of a batch must be independent of each other (no layer's input is another's output), share T, q, q_train
+ * and grad_scale, use bf16 activations and row-wise scales.  Results are bit-identical to the single-layer calls that
+ * run the same streaming kernels.
+ *
+ * Use: fill a HOST array of bcq_batch_layer; bcq_batch_sizes gives the bytes of the plan and of the workspace;
+ * bcq_batch_plan writes the plan into caller-owned HOST memory; the caller copies those bytes to device memory once
+ * (they are position independent); bcq_linear_batched then runs the batch, any number of times, as long as the device
+ * pointers inside the plan stay valid.  Nothing is allocated, copied or retained by the library.
+ *
+ * Fields a given op reads (all device pointers, 16-byte aligned; the others may be NULL):
+ *   BCQ_OP_FWD:       packed [q][N][K/32], alpha [q][N], x [T][K] bf16           -> y [T][N] bf16
+ *   BCQ_OP_BWD_INPUT: packed_t [q][K][N/32] (bcq_pack_transposed), alpha, dy [T][N] bf16 -> dx [T][K] bf16
+ *   BCQ_OP_BWD_ALPHA: packed, x, dy                                              -> dalpha [q_train][N] fp32, overwritten
+ * Limits: 1 <= T <= BCQ_BATCH_MAX_TOKENS, 1 <= q <= BCQ_BATCH_MAX_Q, 1 <= count <= BCQ_BATCH_MAX_LAYERS; the contraction
+ * length (K for forward and scale gradient, N for the input gradient) must be a multiple of 128; else BCQ_ERR_SHAPE.
+ * dtype must be BCQ_BF16 (BCQ_ERR_DTYPE).  q_train and grad_scale are read for BCQ_OP_BWD_ALPHA only. */
+#define BCQ_BATCH_MAX_TOKENS 16
+#define BCQ_BATCH_MAX_Q 4
+#define BCQ_BATCH_MAX_LAYERS (1 << 20)
+typedef struct bcq_batch_layer {
+    const uint32_t* packed;
+    const uint32_t* packed_t;
+    const float* alpha;
+    const void* x;
+    const void* dy;
+    void* y;
+    void* dx;
+    float* dalpha;
+    int64_t N, K;
+} bcq_batch_layer;
+
+/* Bytes of the plan (same size on the host and on the device) and of the device workspace.  Host-only. */
+bcq_status bcq_batch_sizes(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int dtype,
+                           size_t* table_bytes, size_t* workspace_bytes);
+
+/* Writes the plan for `op` over layers[0 .. count) into table_host (HOST memory, at least table_bytes of
+ * bcq_batch_sizes, else BCQ_ERR_WORKSPACE).  Host-only: touches no device.  Checks NULL, shapes, dtype, alignment. */
+bcq_status bcq_batch_plan(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int q_train,
+                          float grad_scale, int dtype, void* table_host, size_t table_bytes);
+
+/* Runs a planned batch on `stream`: table_host is the plan as written by bcq_batch_plan, table_device a copy of the
+ * same bytes in device memory (16-byte aligned; the kernels read it), workspace device scratch of at least the plan's
+ * workspace bytes (16-byte aligned, REQUIRED; contents unspecified afterwards; calls that may overlap need their own).
+ * BCQ_ERR_DTYPE if table_host does not hold a plan of this library version. */
+bcq_status bcq_linear_batched(const void* table_host, const void* table_device, size_t table_bytes, void* workspace,
+                              size_t workspace_bytes, void* stream);
 
 /* One AdamW step (Appendix A: AdamW with a linear-decay learning rate, the schedule being the caller's: pass the
  * step's lr).  Decoupled weight decay, bias-corrected moments, t = step >= 1:

@@ -22,7 +22,7 @@ EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_q
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
            "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
            "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw", "bcq_decode_layout_bytes", "bcq_pack_decode",
-           "bcq_linear_fwd_decode", "bcq_linear_fwd_static")
+           "bcq_linear_fwd_decode", "bcq_linear_fwd_static", "bcq_batch_sizes", "bcq_batch_plan", "bcq_linear_batched")
 
 _lib = None
 
@@ -31,6 +31,13 @@ class AdamW(ctypes.Structure):
     """struct bcq_adamw of include/bcq.h."""
     _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_int64)]
+
+
+class BatchLayer(ctypes.Structure):
+    """struct bcq_batch_layer of include/bcq.h."""
+    _fields_ = [("packed", ctypes.c_void_p), ("packed_t", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+                ("x", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("y", ctypes.c_void_p), ("dx", ctypes.c_void_p),
+                ("dalpha", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
 
 class BcqError(RuntimeError):
@@ -74,6 +81,10 @@ def load():
     lib.bcq_pack_decode.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.bcq_linear_fwd_decode.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_fwd_static.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
+    bl = ctypes.POINTER(BatchLayer)
+    lib.bcq_batch_sizes.argtypes = [i32, bl, i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.bcq_batch_plan.argtypes = [i32, bl, i64, i64, i32, i32, f32, i32, vp, sz]
+    lib.bcq_linear_batched.argtypes = [vp, vp, sz, vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -439,3 +450,51 @@ def bcq_linear_bwd_alpha_adamw(packed, x, dy, g, alpha, m, v, step, lr, beta1=0.
                                              float(grad_scale), _ptr(dalpha), _ptr(alpha), _ptr(m), _ptr(v),
                                              ctypes.byref(opt), wp, wb, _stream()), "bcq_linear_bwd_alpha_adamw")
     return dalpha
+
+
+# ---- batched small-token calls: one operation over many independent layers in two launches ---------------------
+
+class BatchPlan:
+    """A planned batch: the plan bytes on the host and their device copy, the workspace, and the tensors the plan
+    points at (kept alive here).  Run it with bcq_linear_batched(plan), any number of times."""
+
+    def __init__(self, op, T, q, q_train, table_host, table_dev, workspace, keep):
+        self.op, self.T, self.q, self.q_train = op, T, q, q_train
+        self.table_host, self.table_dev, self.workspace, self._keep = table_host, table_dev, workspace, keep
+
+
+def batch_plan(op, layers, T, q, q_train=None, grad_scale=1.0, workspace=None):
+    """layers: list of dicts with the tensors the op reads and writes (bcq_batch_layer of include/bcq.h: packed,
+    packed_t, alpha, x, dy, y, dx, dalpha) plus N and K.  Builds the plan on the host, uploads it, allocates the
+    workspace (or checks the one given)."""
+    q_train = q if q_train is None else int(q_train)
+    n = len(layers)
+    arr = (BatchLayer * n)()
+    keep = []
+    for i, L in enumerate(layers):
+        for name in ("packed", "packed_t", "alpha", "x", "dy", "y", "dx", "dalpha"):
+            t = L.get(name)
+            if t is not None:
+                if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+                    raise ValueError("%s of layer %d must be a contiguous cuda tensor" % (name, i))
+                keep.append(t)
+            setattr(arr[i], name, None if t is None else t.data_ptr())
+        arr[i].N, arr[i].K = int(L["N"]), int(L["K"])
+    tb, wb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load().bcq_batch_sizes(op, arr, n, T, q, BCQ_BF16, ctypes.byref(tb), ctypes.byref(wb)), "bcq_batch_sizes")
+    host = torch.empty((tb.value,), dtype=torch.uint8).pin_memory() if torch.cuda.is_available() else \
+        torch.empty((tb.value,), dtype=torch.uint8)
+    _check(load().bcq_batch_plan(op, arr, n, T, q, q_train, float(grad_scale), BCQ_BF16,
+                                 ctypes.c_void_p(host.data_ptr()), tb.value), "bcq_batch_plan")
+    dev = host.cuda()
+    if workspace is None:
+        workspace = torch.empty((max(wb.value, 16),), dtype=torch.uint8, device=dev.device)
+    elif workspace.numel() * workspace.element_size() < wb.value:
+        raise ValueError("workspace too small: %d bytes needed" % wb.value)
+    return BatchPlan(op, T, q, q_train, host, dev, workspace, keep)
+
+
+def bcq_linear_batched(plan):
+    wp, wbytes = _ws(plan.workspace)
+    _check(load().bcq_linear_batched(ctypes.c_void_p(plan.table_host.data_ptr()), _ptr(plan.table_dev),
+                                     plan.table_host.numel(), wp, wbytes, _stream()), "bcq_linear_batched")

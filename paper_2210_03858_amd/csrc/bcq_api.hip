@@ -133,7 +133,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 6; }
+int bcq_abi_version(void) { return 7; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {

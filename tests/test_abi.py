@@ -144,6 +144,56 @@ def test_fwd_static_errors_before_device(lib):
         assert lib.bcq_linear_fwd_static(A, A, A, 1, 80, N, 12288, q, A, None) == 7  # fits; no device here
 
 
+def test_batch_plan_errors_and_layout_before_device(lib):
+    from paper_2210_03858_amd.binding import BatchLayer
+    sz = ctypes.c_size_t
+    tb, wb = sz(0), sz(0)
+    L = (BatchLayer * 2)()
+    for l, (N, K) in zip(L, ((2560, 2560), (1280, 5120))):
+        l.packed = l.packed_t = l.alpha = l.x = l.dy = l.y = l.dx = l.dalpha = A
+        l.N, l.K = N, K
+    T, q = 8, 4
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
+    # plan: 128-byte header + 128 bytes per layer + 8 bytes per pre-kernel block (5 + 10 segments) and per workgroup
+    # (2560 / 128 + 1280 / 128), rounded up to 256; workspace: (4 x 2048 + 256) bytes per segment at up to 8 tokens
+    assert tb.value == -(-(128 + 2 * 128 + 8 * (15 + 20 + 10)) // 256) * 256
+    assert wb.value == 15 * (4 * 2048 + 256)
+    assert lib.bcq_batch_sizes(2, L, 2, 16, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
+    assert wb.value == q * 2 * (5 + 3) * (4 * 2048 + 256)  # one set per plane, two operand halves, N / 512 rounded up
+    assert lib.bcq_batch_sizes(1, None, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 1
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, 1, None, ctypes.byref(wb)) == 1
+    assert lib.bcq_batch_sizes(0, L, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 3     # not a batched op
+    assert lib.bcq_batch_sizes(1, L, 0, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2
+    assert lib.bcq_batch_sizes(1, L, 2, 17, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2    # at most 16 tokens
+    assert lib.bcq_batch_sizes(1, L, 2, T, 5, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2     # at most 4 planes
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, 0, ctypes.byref(tb), ctypes.byref(wb)) == 3     # bf16 only
+    L[1].K = 5120 + 32
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2     # K % 128 != 0
+    assert lib.bcq_batch_sizes(2, L, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0     # dx contracts over N
+    L[1].K = 5120
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
+    buf = ctypes.create_string_buffer(tb.value)
+    assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, buf, tb.value - 1) == 5
+    assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, None, tb.value) == 1
+    assert lib.bcq_batch_plan(3, L, 2, T, q, 0, 1.0, 1, buf, tb.value) == 2                   # q_train outside [1, q]
+    L[0].y = None
+    assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, buf, tb.value) == 1
+    assert lib.bcq_batch_plan(3, L, 2, T, q, q, 1.0, 1, buf, tb.value) == 0                   # dalpha does not read y
+    L[0].y = A + 4
+    assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, buf, tb.value) == 4
+    L[0].y = A
+    assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, buf, tb.value) == 0
+    # run: checks that need no device come first
+    assert lib.bcq_linear_batched(buf, None, tb.value, A, 1 << 30, None) == 1
+    assert lib.bcq_linear_batched(buf, A, tb.value, A, 16, None) == 5                          # workspace too small
+    assert lib.bcq_linear_batched(buf, A + 8, tb.value, A, 1 << 30, None) == 4
+    junk = ctypes.create_string_buffer(tb.value)
+    assert lib.bcq_linear_batched(junk, A, tb.value, A, 1 << 30, None) == 3                    # not a plan
+    import torch
+    if not torch.cuda.is_available():
+        assert lib.bcq_linear_batched(buf, A, tb.value, A, 1 << 30, None) == 7
+
+
 def test_no_device_is_reported(lib):
     import torch
     if torch.cuda.is_available():
