@@ -259,9 +259,10 @@ typedef struct bcq_batch_layer {
     int64_t N, K;
 } bcq_batch_layer;
 
-/* Bytes of the plan (same size on the host and on the device) and of the device workspace.  Host-only. */
-bcq_status bcq_batch_sizes(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int dtype,
-                           size_t* table_bytes, size_t* workspace_bytes);
+/* Bytes of the plan (same size on the host and on the device) and of the device workspace for these arguments (the
+ * same op, layers, T, q, q_train must be given to bcq_batch_plan).  Host-only. */
+bcq_status bcq_batch_sizes(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int q_train,
+                           int dtype, size_t* table_bytes, size_t* workspace_bytes);
 
 /* Writes the plan for `op` over layers[0 .. count) into table_host (HOST memory, at least table_bytes of
  * bcq_batch_sizes, else BCQ_ERR_WORKSPACE).  Host-only: touches no device.  Checks NULL, shapes, dtype, alignment. */

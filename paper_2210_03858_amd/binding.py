@@ -82,7 +82,7 @@ def load():
     lib.bcq_linear_fwd_decode.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_fwd_static.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
     bl = ctypes.POINTER(BatchLayer)
-    lib.bcq_batch_sizes.argtypes = [i32, bl, i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.bcq_batch_sizes.argtypes = [i32, bl, i64, i64, i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.bcq_batch_plan.argtypes = [i32, bl, i64, i64, i32, i32, f32, i32, vp, sz]
     lib.bcq_linear_batched.argtypes = [vp, vp, sz, vp, sz, vp]
     for name in EXPORTS[2:]:
@@ -481,7 +481,8 @@ def batch_plan(op, layers, T, q, q_train=None, grad_scale=1.0, workspace=None):
             setattr(arr[i], name, None if t is None else t.data_ptr())
         arr[i].N, arr[i].K = int(L["N"]), int(L["K"])
     tb, wb = ctypes.c_size_t(0), ctypes.c_size_t(0)
-    _check(load().bcq_batch_sizes(op, arr, n, T, q, BCQ_BF16, ctypes.byref(tb), ctypes.byref(wb)), "bcq_batch_sizes")
+    _check(load().bcq_batch_sizes(op, arr, n, T, q, q_train, BCQ_BF16, ctypes.byref(tb), ctypes.byref(wb)),
+           "bcq_batch_sizes")
     host = torch.empty((tb.value,), dtype=torch.uint8).pin_memory() if torch.cuda.is_available() else \
         torch.empty((tb.value,), dtype=torch.uint8)
     _check(load().bcq_batch_plan(op, arr, n, T, q, q_train, float(grad_scale), BCQ_BF16,
