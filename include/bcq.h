@@ -227,10 +227,15 @@ bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, c
  * in proportion to the memory reduction.  A single layer of the paper's models holds only 0.2 - 13 MB of sign planes
  * (Table 1), less than a microsecond of HBM time, so a call per layer is bound by launches.  These entry points run
  * ONE operation - forward (Eq. 2), input gradient (Eq. 3) or scale gradient (Eq. 4) - for `count` layers at once:
- * one activation re-coding launch and one streaming launch whose workgroups look their layer up in a plan.
+ * one activation re-coding launch and one streaming launch whose workgroups look their share of the work up in a plan.
  * The layers of a batch must be independent of each other (no layer's input is another's output), share T, q, q_train
- * and grad_scale, use bf16 activations and row-wise scales.  Results are bit-identical to the single-layer calls that
- * run the same streaming kernels.
+ * and grad_scale, use bf16 activations and row-wise scales.  Same arithmetic as the single-layer streaming kernels
+ * (signs times activations split into two FP8 terms on the block-scaled matrix instruction, fp32 accumulation).
+ *
+ * The planes are read in the DECODE layout (bcq_pack_decode), which a wave can stream in address order:
+ *   tiled    = bcq_pack_decode(packed,   N, K, q)   for the forward and the scale gradient,
+ *   tiled_t  = bcq_pack_decode(packed_t, K, N, q)   for the input gradient (the decode layout of the transposed twin,
+ *              i.e. of the [q][K][N/32] matrix that bcq_pack_transposed builds; needs N % 32 == 0).
  *
  * Use: fill a HOST array of bcq_batch_layer; bcq_batch_sizes gives the bytes of the plan and of the workspace;
  * bcq_batch_plan writes the plan into caller-owned HOST memory; the caller copies those bytes to device memory once
@@ -238,18 +243,18 @@ bcq_status bcq_linear_bwd_alpha_grouped(const uint32_t* packed, const void* x, c
  * pointers inside the plan stay valid.  Nothing is allocated, copied or retained by the library.
  *
  * Fields a given op reads (all device pointers, 16-byte aligned; the others may be NULL):
- *   BCQ_OP_FWD:       packed [q][N][K/32], alpha [q][N], x [T][K] bf16           -> y [T][N] bf16
- *   BCQ_OP_BWD_INPUT: packed_t [q][K][N/32] (bcq_pack_transposed), alpha, dy [T][N] bf16 -> dx [T][K] bf16
- *   BCQ_OP_BWD_ALPHA: packed, x, dy                                              -> dalpha [q_train][N] fp32, overwritten
- * Limits: 1 <= T <= BCQ_BATCH_MAX_TOKENS, 1 <= q <= BCQ_BATCH_MAX_Q, 1 <= count <= BCQ_BATCH_MAX_LAYERS; the contraction
- * length (K for forward and scale gradient, N for the input gradient) must be a multiple of 128; else BCQ_ERR_SHAPE.
- * dtype must be BCQ_BF16 (BCQ_ERR_DTYPE).  q_train and grad_scale are read for BCQ_OP_BWD_ALPHA only. */
+ *   BCQ_OP_FWD:       tiled, alpha [q][N], x [T][K] bf16        -> y [T][N] bf16
+ *   BCQ_OP_BWD_INPUT: tiled_t, alpha, dy [T][N] bf16            -> dx [T][K] bf16
+ *   BCQ_OP_BWD_ALPHA: tiled, x, dy                              -> dalpha [q_train][N] fp32, overwritten
+ * Limits: 1 <= T <= BCQ_BATCH_MAX_TOKENS, 1 <= q <= BCQ_BATCH_MAX_Q, 1 <= count <= BCQ_BATCH_MAX_LAYERS, N % 32 == 0
+ * for the input gradient; else BCQ_ERR_SHAPE.  dtype must be BCQ_BF16 (BCQ_ERR_DTYPE).  q_train and grad_scale are read
+ * for BCQ_OP_BWD_ALPHA only. */
 #define BCQ_BATCH_MAX_TOKENS 16
 #define BCQ_BATCH_MAX_Q 4
 #define BCQ_BATCH_MAX_LAYERS (1 << 20)
 typedef struct bcq_batch_layer {
-    const uint32_t* packed;
-    const uint32_t* packed_t;
+    const uint32_t* tiled;
+    const uint32_t* tiled_t;
     const float* alpha;
     const void* x;
     const void* dy;

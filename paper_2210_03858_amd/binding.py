@@ -35,7 +35,7 @@ class AdamW(ctypes.Structure):
 
 class BatchLayer(ctypes.Structure):
     """struct bcq_batch_layer of include/bcq.h."""
-    _fields_ = [("packed", ctypes.c_void_p), ("packed_t", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+    _fields_ = [("tiled", ctypes.c_void_p), ("tiled_t", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("x", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("y", ctypes.c_void_p), ("dx", ctypes.c_void_p),
                 ("dalpha", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
 
@@ -464,15 +464,16 @@ class BatchPlan:
 
 
 def batch_plan(op, layers, T, q, q_train=None, grad_scale=1.0, workspace=None):
-    """layers: list of dicts with the tensors the op reads and writes (bcq_batch_layer of include/bcq.h: packed,
-    packed_t, alpha, x, dy, y, dx, dalpha) plus N and K.  Builds the plan on the host, uploads it, allocates the
+    """layers: list of dicts with the tensors the op reads and writes (bcq_batch_layer of include/bcq.h: tiled,
+    tiled_t, alpha, x, dy, y, dx, dalpha) plus N and K; tiled = bcq_pack_decode(packed), tiled_t =
+    bcq_pack_decode(bcq_pack_transposed(packed)).  Builds the plan on the host, uploads it, allocates the
     workspace (or checks the one given)."""
     q_train = q if q_train is None else int(q_train)
     n = len(layers)
     arr = (BatchLayer * n)()
     keep = []
     for i, L in enumerate(layers):
-        for name in ("packed", "packed_t", "alpha", "x", "dy", "y", "dx", "dalpha"):
+        for name in ("tiled", "tiled_t", "alpha", "x", "dy", "y", "dx", "dalpha"):
             t = L.get(name)
             if t is not None:
                 if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):

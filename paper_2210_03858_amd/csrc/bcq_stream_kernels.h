@@ -134,7 +134,8 @@ template <int MODE>
 __device__ __forceinline__ void quant_act_body(const bf16_t* __restrict__ act, const float* __restrict__ alpha,
                                                int64_t T, int64_t C, int64_t segs, int halves, int tiles,
                                                unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
-                                               size_t xq_plane, size_t sq_plane, int NG, uint32_t bx, uint32_t by) {
+                                               size_t xq_plane, size_t sq_plane, int NG, int seg_mul, uint32_t bx,
+                                               uint32_t by) {
     const int64_t idx = (int64_t)bx * 256 + threadIdx.x;
     const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
     const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
@@ -160,8 +161,9 @@ __device__ __forceinline__ void quant_act_body(const bf16_t* __restrict__ act, c
 #pragma unroll
         for (int e = 0; e < 32; ++e) v[e] = 0.f;
     }
-    recode_unit(v, tl, G, j, one_half, xq + ((size_t)(tile * segs + seg) * 4 + j) * halves * QBLK,
-                sq + (size_t)(tile * segs + seg) * halves * QSCL);
+    // seg_mul > 1 interleaves the sets: block (segment, set) at index segment * seg_mul + set (xq_plane, sq_plane = one block)
+    recode_unit(v, tl, G, j, one_half, xq + ((size_t)(tile * segs + seg) * seg_mul * 4 + j) * halves * QBLK,
+                sq + (size_t)(tile * segs + seg) * seg_mul * halves * QSCL);
 }
 
 template <int MODE>
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const bf16_t* __restrict
                                                         int64_t T, int64_t C, int64_t segs, int halves, int tiles,
                                                         unsigned char* __restrict__ xq, unsigned char* __restrict__ sq,
                                                         size_t xq_plane, size_t sq_plane, int NG) {
-    quant_act_body<MODE>(act, alpha, T, C, segs, halves, tiles, xq, sq, xq_plane, sq_plane, NG, blockIdx.x, blockIdx.y);
+    quant_act_body<MODE>(act, alpha, T, C, segs, halves, tiles, xq, sq, xq_plane, sq_plane, NG, 1, blockIdx.x, blockIdx.y);
 }
 
 // ---------------------------------------------------------------------------------------------------------

@@ -150,15 +150,15 @@ def test_batch_plan_errors_and_layout_before_device(lib):
     tb, wb = sz(0), sz(0)
     L = (BatchLayer * 2)()
     for l, (N, K) in zip(L, ((2560, 2560), (1280, 5120))):
-        l.packed = l.packed_t = l.alpha = l.x = l.dy = l.y = l.dx = l.dalpha = A
+        l.tiled = l.tiled_t = l.alpha = l.x = l.dy = l.y = l.dx = l.dalpha = A
         l.N, l.K = N, K
     T, q = 8, 4
     assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
     # plan: 128-byte header + 128 bytes per layer + 8 bytes per pre-kernel block (5 + 10 segments) + 16 bytes per piece
-    # (160 row tiles in pieces of 20; 80 row tiles of the 10-segment layer in pieces of 32), rounded up to 256;
-    # workspace: (4 x 2048 + 256) bytes per segment at up to 8 tokens + 1 KiB per row tile of the layer with two chunks
-    assert tb.value == -(-(128 + 2 * 128 + 8 * 15 + 16 * (8 + 3)) // 256) * 256
-    assert wb.value == 15 * (4 * 2048 + 256) + 80 * 1024
+    # (160 row tiles in pieces of 20; 80 row tiles of the 10-segment, two-chunk layer in pieces of 16), rounded up to
+    # 256; workspace: (4 x 2048 + 256) bytes per segment at up to 8 tokens
+    assert tb.value == -(-(128 + 2 * 128 + 8 * 15 + 16 * (8 + 5)) // 256) * 256
+    assert wb.value == 15 * (4 * 2048 + 256)
     assert lib.bcq_batch_sizes(2, L, 2, 16, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
     assert wb.value == q * 2 * (5 + 3) * (4 * 2048 + 256)  # one set per plane, two operand halves, N / 512 rounded up
     assert lib.bcq_batch_sizes(1, None, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 1
@@ -168,11 +168,13 @@ def test_batch_plan_errors_and_layout_before_device(lib):
     assert lib.bcq_batch_sizes(1, L, 2, 17, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2    # at most 16 tokens
     assert lib.bcq_batch_sizes(1, L, 2, T, 5, 5, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2     # at most 4 planes
     assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 0, ctypes.byref(tb), ctypes.byref(wb)) == 3     # bf16 only
-    L[1].K = 5120 + 32
-    assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2  # K % 128 != 0
-    assert lib.bcq_batch_sizes(2, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0  # dx contracts over N
+    L[1].K = 5120 + 16
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2  # K % 32 != 0
+    L[1].K, L[1].N = 5120, 1280 + 16
+    assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
+    assert lib.bcq_batch_sizes(2, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2  # dx: the twin needs N % 32 == 0
     assert lib.bcq_batch_sizes(3, L, 2, T, q, 0, 1, ctypes.byref(tb), ctypes.byref(wb)) == 2  # q_train outside [1, q]
-    L[1].K = 5120
+    L[1].N = 1280
     assert lib.bcq_batch_sizes(1, L, 2, T, q, q, 1, ctypes.byref(tb), ctypes.byref(wb)) == 0
     buf = ctypes.create_string_buffer(tb.value)
     assert lib.bcq_batch_plan(1, L, 2, T, q, q, 1.0, 1, buf, tb.value - 1) == 5

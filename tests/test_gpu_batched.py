@@ -27,8 +27,10 @@ def _make_batch(bcq, oracle, config, shapes, T, q, poison=True):
     for kind, N, K, extra in shapes:
         W, alpha, planes, packed, x, dy = make_case(config, kind, T, N, K, q, "bf16", oracle, extra=extra)
         d_packed = packed_to_dev(packed)
-        L = dict(N=N, K=K, packed=d_packed, alpha=to_dev(alpha), x=to_dev(x, "bf16"), dy=to_dev(dy, "bf16"),
-                 packed_t=bcq.bcq_pack_transposed(d_packed) if N % 32 == 0 else None,
+        L = dict(N=N, K=K, tiled=bcq.bcq_pack_decode(d_packed), alpha=to_dev(alpha), x=to_dev(x, "bf16"),
+                 dy=to_dev(dy, "bf16"),
+                 # decode layout of the transposed twin [q][K][N/32]
+                 tiled_t=bcq.bcq_pack_decode(bcq.bcq_pack_transposed(d_packed)) if N % 32 == 0 else None,
                  # outputs start as NaN: every element must be written by the batch
                  y=torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda"),
                  dx=torch.full((T, K), float("nan"), dtype=torch.bfloat16, device="cuda"),
@@ -60,7 +62,7 @@ def _check_batch(bcq, oracle, layers, T, q, ops=(OP_FWD, OP_DX, OP_DALPHA), q_tr
 
 
 MIXED = [("out", 256, 128, 0), ("qkv", 1000, 1280, 1), ("mlp_up", 48, 2560, 2), ("mlp_down", 1040, 640, 3),
-         ("out", 16, 4096 + 128, 4), ("qkv", 2056, 384, 5)]
+         ("out", 16, 4096 + 128, 4), ("qkv", 2056, 384, 5), ("out", 70, 32 * 37, 6)]  # K % 128 != 0
 
 
 @pytest.mark.parametrize("T,q", [(1, 1), (3, 2), (8, 4), (9, 3), (16, 4)])
@@ -71,18 +73,16 @@ def test_batched_fwd_and_dalpha_mixed_ragged_shapes(bcq, oracle, T, q):
     _check_batch(bcq, oracle, layers, T, q, ops=(OP_FWD, OP_DALPHA))
 
 
-MIXED_DX = [("out", 512, 256, 0),        # N % 512 == 0: shared-activation form
-            ("qkv", 1280, 992, 1),      # N % 512 != 0: per-wave form; ragged K (rows of the twin)
-            ("mlp_up", 1024, 2560, 2), ("mlp_down", 128, 640, 3), ("out", 3840, 64, 4), ("qkv", 1536, 4128, 5)]
+MIXED_DX = [("out", 512, 256, 0), ("qkv", 1280, 992, 1),  # N = 2.5 segments; ragged K (rows of the twin)
+            ("mlp_up", 1024, 2560, 2), ("mlp_down", 128, 640, 3), ("out", 3840, 64, 4), ("qkv", 1536, 4128, 5),
+            ("out", 96, 32, 6)]           # N % 128 != 0, a single 32-column word of K
 
 
 @pytest.mark.parametrize("T,q", [(1, 1), (5, 2), (8, 4), (12, 3), (16, 4)])
-def test_batched_input_gradient_mixed_forms(bcq, oracle, T, q):
-    """Both forms of the input gradient in one batch (two main launches), and each alone."""
+def test_batched_input_gradient_mixed_shapes(bcq, oracle, T, q):
+    """Input gradient: one virtual plane over q x ceil(N / 512) virtual segments; one to 8 chunks, ragged rows."""
     layers = _make_batch(bcq, oracle, 3, MIXED_DX, T, q)
     _check_batch(bcq, oracle, layers, T, q, ops=(OP_DX,))
-    _check_batch(bcq, oracle, [L for L in layers if L["N"] % 512 == 0], T, q, ops=(OP_DX,))
-    _check_batch(bcq, oracle, [L for L in layers if L["N"] % 512 != 0], T, q, ops=(OP_DX,))
 
 
 def test_batched_q_train_and_grad_scale(bcq, oracle):
@@ -152,12 +152,12 @@ def test_batched_errors(bcq):
     import torch
     T, q, N, K = 4, 2, 256, 256
     z = lambda *s, dt=torch.bfloat16: torch.zeros(s, dtype=dt, device="cuda")
-    base = dict(N=N, K=K, packed=z(q, N, K // 32, dt=torch.int32), packed_t=z(q, K, N // 32, dt=torch.int32),
+    base = dict(N=N, K=K, tiled=z(q * N * K // 32, dt=torch.int32), tiled_t=z(q * N * K // 32, dt=torch.int32),
                 alpha=z(q, N, dt=torch.float32), x=z(T, K), dy=z(T, N), y=z(T, N), dx=z(T, K),
                 dalpha=z(q, N, dt=torch.float32))
-    for bad, status in ((dict(K=160), 2), (dict(y=None), 1)):
+    for op, bad, status in ((OP_FWD, dict(K=48), 2), (OP_FWD, dict(y=None), 1), (OP_DX, dict(N=48), 2)):
         with pytest.raises(bcq.BcqError) as e:
-            bcq.batch_plan(OP_FWD, [dict(base, **bad)], T, q)
+            bcq.batch_plan(op, [dict(base, **bad)], T, q)
         assert e.value.status == status
     with pytest.raises(bcq.BcqError) as e:
         bcq.batch_plan(OP_FWD, [base], 17, q)
