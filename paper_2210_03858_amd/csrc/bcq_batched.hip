@@ -19,6 +19,7 @@
 #include "bcq_stream_kernels.h"
 
 #include <algorithm>
+#include <functional>
 #include <string.h>
 #include <vector>
 
@@ -161,24 +162,66 @@ __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const Batch
     const int64_t piece_row0 = (int64_t)P.rtg0 * RT * 16;
     unsigned char* const part = aux + tile_ep_bytes(MODE, QP, RT, (int)P.nrtg, H);  // this piece's carried sums
 
-    // epilogue operands of the piece -> LDS (visible after the first chunk copy's barriers)
-    if (MODE == STREAM_FWD) {  // alpha[i][row] * (-1/6) as fp32, [QP][piece_rows]
-        BCQ_GLOBAL const float* const alpha = (BCQ_GLOBAL const float*)L.alpha;
-        float* dst = reinterpret_cast<float*>(aux);
-        for (int e = tid; e < QP * piece_rows; e += 64 * TILE_WAVES) {
-            const int i = e / piece_rows, lr = e - i * piece_rows;
-            const int64_t n = piece_row0 + lr;
-            dst[e] = n < rows ? alpha[(int64_t)i * rows + n] * FIX : 0.f;
-        }
-    } else if (DA) {  // dy[t][row] as bf16, [TT][piece_rows]; tokens beyond T and rows beyond the matrix as zeros
-        BCQ_GLOBAL const bf16_t* const dy = (BCQ_GLOBAL const bf16_t*)L.dy;
-        bf16_t* dst = reinterpret_cast<bf16_t*>(aux);
-        for (int e = tid; e < TT * piece_rows; e += 64 * TILE_WAVES) {
-            const int t = e / piece_rows, lr = e - t * piece_rows;
-            const int64_t n = piece_row0 + lr;
-            dst[e] = (t < T && n < rows) ? dy[(int64_t)t * rows + n] : (bf16_t)0;
+    // Epilogue operands of the piece: requested here into registers (up to three 16-byte vectors per thread), written to
+    // LDS together with the first chunk of activations, so that all start-up requests of the workgroup are in flight
+    // at once (one memory round trip instead of one per loop iteration).
+    //   forward: alpha[i][row] * (-1/6) as fp32, [QP][piece_rows]
+    //   scale gradient: dy[t][row] as bf16, [TT][piece_rows]; tokens beyond T and rows beyond the matrix as zeros
+    constexpr int EPV = 3;
+    q_u32x4 epv[EPV];
+    const int ep_per = MODE == STREAM_FWD ? piece_rows / 4 : piece_rows / 8;  // vectors per plane / per token
+    const int ep_total = DX ? 0 : (MODE == STREAM_FWD ? QP : TT) * ep_per;
+    const bool ep_vec = DX || (MODE == STREAM_FWD ? (rows & 3) == 0 : (rows & 7) == 0);  // rows start 16-byte aligned
+    if (!DX && ep_vec) {
+#pragma unroll
+        for (int it = 0; it < EPV; ++it) {
+            const int e = tid + it * 64 * TILE_WAVES;
+            epv[it] = q_u32x4{0u, 0u, 0u, 0u};
+            if (e < ep_total) {
+                const int a = e / ep_per, lv = e - a * ep_per;  // plane or token, vector inside its row of the table
+                if (MODE == STREAM_FWD) {
+                    const int64_t n = piece_row0 + 4 * lv;
+                    if (n < rows) epv[it] = *(BCQ_GLOBAL const q_u32x4*)((BCQ_GLOBAL const float*)L.alpha + (int64_t)a * rows + n);
+                } else {
+                    const int64_t n = piece_row0 + 8 * lv;
+                    if (a < T && n < rows) epv[it] = *(BCQ_GLOBAL const q_u32x4*)((BCQ_GLOBAL const bf16_t*)L.dy + (int64_t)a * rows + n);
+                }
+            }
         }
     }
+    auto store_ep = [&]() {
+        if (DX) return;
+        if (ep_vec) {
+#pragma unroll
+            for (int it = 0; it < EPV; ++it) {
+                const int e = tid + it * 64 * TILE_WAVES;
+                if (e < ep_total) {
+                    q_u32x4 v = epv[it];
+                    if (MODE == STREAM_FWD) {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) v[x] = __float_as_uint(__uint_as_float(v[x]) * FIX);
+                    }
+                    reinterpret_cast<q_u32x4*>(aux)[e] = v;
+                }
+            }
+        } else if (MODE == STREAM_FWD) {  // rows not a multiple of 4: element by element
+            BCQ_GLOBAL const float* const alpha = (BCQ_GLOBAL const float*)L.alpha;
+            float* dst = reinterpret_cast<float*>(aux);
+            for (int e = tid; e < QP * piece_rows; e += 64 * TILE_WAVES) {
+                const int i = e / piece_rows, lr = e - i * piece_rows;
+                const int64_t n = piece_row0 + lr;
+                dst[e] = n < rows ? alpha[(int64_t)i * rows + n] * FIX : 0.f;
+            }
+        } else {  // rows not a multiple of 8
+            BCQ_GLOBAL const bf16_t* const dy = (BCQ_GLOBAL const bf16_t*)L.dy;
+            bf16_t* dst = reinterpret_cast<bf16_t*>(aux);
+            for (int e = tid; e < TT * piece_rows; e += 64 * TILE_WAVES) {
+                const int t = e / piece_rows, lr = e - t * piece_rows;
+                const int64_t n = piece_row0 + lr;
+                dst[e] = (t < T && n < rows) ? dy[(int64_t)t * rows + n] : (bf16_t)0;
+            }
+        }
+    };
 
     // ---- the ring of plane words
     uint32_t bits[TILE_RING][PR][4];
@@ -238,30 +281,23 @@ __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const Batch
     for (int c = 0; c < nchunks; ++c) {
         const int seg0 = c * cseg;
         const int nseg = chunk_nseg(c);
-        // chunk copy: nseg x H operand-block sets of 8 KiB + nseg x H x 256 B of scales, global -> registers -> LDS,
-        // eight 4 KiB units (256 threads x 16 B) at a time
+        // chunk copy: nseg x H operand-block sets of 8 KiB + nseg x H x 256 B of scales, global -> registers -> LDS; all
+        // (up to sixteen) 4 KiB units of 256 threads x 16 B are requested before the first is written
         {
             const q_u32x4* src = reinterpret_cast<const q_u32x4*>(xq + (size_t)seg0 * (4 * H * QBLK)) + tid;
             q_u32x4* dst = reinterpret_cast<q_u32x4*>(xb) + tid;
             const int nx = nseg * H * 2;
-            q_u32x4 st[8], sts = {0u, 0u, 0u, 0u};
+            q_u32x4 st[16], sts = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int it = 0; it < 8; ++it)
+            for (int it = 0; it < 16; ++it)
                 if (it < nx) st[it] = src[it * 256];
             if (tid < nseg * H * 16) sts = reinterpret_cast<const q_u32x4*>(sq + (size_t)seg0 * (H * QSCL))[tid];
             __syncthreads();  // every wave is done reading the previous chunk
+            if (c == 0) store_ep();
 #pragma unroll
-            for (int it = 0; it < 8; ++it)
+            for (int it = 0; it < 16; ++it)
                 if (it < nx) dst[it * 256] = st[it];
             if (tid < nseg * H * 16) reinterpret_cast<q_u32x4*>(sb)[tid] = sts;
-            if (nx > 8) {  // uniform
-#pragma unroll
-                for (int it = 0; it < 8; ++it)
-                    if (8 + it < nx) st[it] = src[(8 + it) * 256];
-#pragma unroll
-                for (int it = 0; it < 8; ++it)
-                    if (8 + it < nx) dst[(8 + it) * 256] = st[it];
-            }
             __syncthreads();
         }
         if (nk == 0) continue;  // a wave without groups only helps with the copies
@@ -434,14 +470,17 @@ static inline int tile_qp(int op, int q_used) { return op == BCQ_OP_BWD_INPUT ? 
 // fit the LDS area)
 static inline int tile_rt(int qp, int halves) { return qp == 1 ? (halves == 2 ? 2 : 4) : (qp == 2 ? 2 : 1); }
 
-// Work of one workgroup, in units of (row-tile group x segment).  Small enough that the launch ends without a long
-// tail (the pieces are started longest first), large enough that the chunk copies (one per piece and chunk, 8 KiB per
-// segment and operand half) stay a small part of the plane bytes; layers with several chunks get longer pieces
-// because every chunk of a piece costs a copy with a barrier on either side.
-constexpr int kTileUnitsPerPiece = 96;
-constexpr int kTileUnitsPerPieceMulti = 320;
+// Work of one workgroup (a piece), in units of (row-tile group x segment).  The hardware starts the pieces in
+// index order as slots free up (two workgroups per compute unit of the 256), the longest first.  The size is chosen
+// per batch (choose_piece_units): small enough that the last round of pieces is not half empty, large enough that
+// the start-up of a piece (plan look-up, first memory round trip, one activation copy with two barriers per chunk)
+// stays a small part of its streaming time.  Layers with several chunks get pieces of three times the size.
+constexpr int kTileSlots = 512;
+constexpr int kTileStartupUnits = 12;       // start-up of a piece, in units of streaming time (about 4 us)
+constexpr int kTileChunkStartupUnits = 7;   // every further chunk: a copy between two barriers
+constexpr int kTileMultiFactor = 3;
 
-static BatchShape batch_shape(int op, int64_t T, int64_t N, int64_t K, int q, int q_used) {
+static BatchShape batch_shape(int op, int64_t T, int64_t N, int64_t K, int q, int q_used, int piece_units) {
     BatchShape s = {};
     const bool dx = (op == BCQ_OP_BWD_INPUT);
     const int halves = T <= 8 ? 1 : 2;
@@ -473,7 +512,7 @@ static BatchShape batch_shape(int op, int64_t T, int64_t N, int64_t K, int q, in
     s.chunk_segs = (s.segs_main + nch - 1) / nch;  // chunks of about equal length
     const bool multi = nch > 1;
     const int mode = dx ? STREAM_DX : (op == BCQ_OP_FWD ? STREAM_FWD : STREAM_DALPHA);
-    const int target = multi ? kTileUnitsPerPieceMulti : kTileUnitsPerPiece;
+    const int target = multi ? kTileMultiFactor * piece_units : piece_units;
     int per = (target + s.segs_main - 1) / s.segs_main;
     per = (per + TILE_WAVES - 1) / TILE_WAVES * TILE_WAVES;  // whole rounds of the four waves
     if (per < TILE_WAVES) per = TILE_WAVES;
@@ -490,7 +529,46 @@ static_assert(tile_ep_bytes(STREAM_DALPHA, 1, 4, TILE_WAVES, 1) + tile_part_byte
 static_assert(tile_ep_bytes(STREAM_DALPHA, 1, 2, TILE_WAVES, 2) + tile_part_bytes(2, TILE_WAVES, 2) <= TILE_AUX, "");
 static_assert(tile_ep_bytes(STREAM_FWD, 4, 1, TILE_WAVES, 2) + tile_part_bytes(1, TILE_WAVES, 2) <= TILE_AUX, "");
 
+// Picks the piece size for a batch: list scheduling (longest piece first, 512 slots) of the pieces every candidate size
+// gives, with the start-up costs above; the candidate with the shortest schedule wins.  Pure host arithmetic.
+static int choose_piece_units(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int q_used) {
+    int best = 96;
+    double best_span = -1.0;
+    std::vector<int64_t> costs;
+    std::vector<int64_t> slots;
+    for (int cand = 48; cand <= 240; cand += 8) {
+        costs.clear();
+        for (int64_t l = 0; l < count; ++l) {
+            const BatchShape s = batch_shape(op, T, layers[l].N, layers[l].K, q, q_used, cand);
+            const int nch = (s.segs_main + s.chunk_segs - 1) / s.chunk_segs;
+            const int64_t fixed = kTileStartupUnits + (int64_t)(nch - 1) * kTileChunkStartupUnits;
+            for (int32_t r0 = 0; r0 < s.nrtg; r0 += s.piece_rtg) {
+                const int32_t n = (s.nrtg - r0) < s.piece_rtg ? (s.nrtg - r0) : s.piece_rtg;
+                // the four waves take the groups in rounds: a piece lasts as long as its busiest wave
+                const int64_t rounds = (n + TILE_WAVES - 1) / TILE_WAVES;
+                costs.push_back(rounds * TILE_WAVES * (int64_t)s.segs_main + fixed);
+            }
+        }
+        std::sort(costs.begin(), costs.end(), [](int64_t a, int64_t b) { return a > b; });
+        slots.assign(kTileSlots, 0);
+        std::make_heap(slots.begin(), slots.end(), std::greater<int64_t>());
+        int64_t span = 0;
+        for (int64_t c : costs) {
+            std::pop_heap(slots.begin(), slots.end(), std::greater<int64_t>());
+            slots.back() += c;
+            span = slots.back() > span ? slots.back() : span;
+            std::push_heap(slots.begin(), slots.end(), std::greater<int64_t>());
+        }
+        if (best_span < 0 || (double)span < best_span * 0.995) {  // ties go to the smaller size
+            best_span = (double)span;
+            best = cand;
+        }
+    }
+    return best;
+}
+
 struct BatchTotals {
+    int piece_units = 96;
     uint64_t pre_blocks = 0, pieces = 0;
     size_t table_bytes = 0, workspace_bytes = 0;
     uint64_t plane_bytes = 0;
@@ -498,8 +576,9 @@ struct BatchTotals {
 
 static BatchTotals batch_totals(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int q_used) {
     BatchTotals t;
+    t.piece_units = choose_piece_units(op, layers, count, T, q, q_used);
     for (int64_t l = 0; l < count; ++l) {
-        const BatchShape s = batch_shape(op, T, layers[l].N, layers[l].K, q, q_used);
+        const BatchShape s = batch_shape(op, T, layers[l].N, layers[l].K, q, q_used, t.piece_units);
         t.pre_blocks += (uint64_t)s.segs_act;
         t.pieces += s.pieces;
         t.workspace_bytes += align_up(s.xq_bytes, 256) + align_up(s.sq_bytes, 256);
@@ -641,7 +720,7 @@ bcq_status bcq_batch_plan(int op, const bcq_batch_layer* layers, int64_t count, 
     uint64_t pb = 0;
     for (int64_t l = 0; l < count; ++l) {
         const bcq_batch_layer& b = layers[l];
-        const BatchShape sh = batch_shape(op, T, b.N, b.K, q, q_used);
+        const BatchShape sh = batch_shape(op, T, b.N, b.K, q, q_used, t.piece_units);
         BatchLayerDev d = {};
         d.planes = (op == BCQ_OP_BWD_INPUT) ? b.tiled_t : b.tiled;
         d.alpha = b.alpha;
