@@ -1,19 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the BCQ linear hot path on one MI355X.
 
-Workload (default): the four linear layers of one GPT-2-medium-shaped block (h = 1024: QKV 1024->3072,
-out 1024->1024, MLP 1024->4096->1024), q = 4 bit planes, bf16 activations, T = 8 x 512 = 4096 tokens,
-W ~ N(0, 0.02^2) quantized once by the greedy quantizer, x, dy ~ N(0, 1).  One step = forward, input gradient
-and alpha gradient of all four layers.  The quantizer, pack and transposed-twin passes run once before the
-timed region (they are the one-time PTQ of the method) and are timed separately in "setup".
+One step = forward, input gradient and alpha gradient of every layer of the workload.  The quantizer, pack,
+transposed-twin and decode-layout passes run once before the timed regions (they are the one-time PTQ of the method)
+and are timed separately in "setup".
 
-Prints ONE JSON line: effective TFLOP/s (6 T N K flops per layer and step), the roofline figures of the
-dominant kernel family measured with HIP events inside the timed region, and the CPU oracle timed on a bounded
-sample of the same workload.
+The default run prints ONE JSON line:
+  * headline (`value`, `config`, `roofline`): the largest large-token workload, number 4 of the benchmark definition:
+    the four linear layers of an OPT-1.3B-shaped block (d = 2048, MLP 8192), q = 3, 0.1 % outlier rows, bf16
+    activations, T = 8 x 2048 = 16384 tokens, full fwd + dx + dalpha.  `--steps` steps are timed exactly.
+  * `regimes`: the other regimes the targets are stated on, each with ms_per_step, effective TFLOP/s, packed-weight
+    GB/s and its own roofline object: workload 2 (GPT-2-medium block, T = 4096), workload 5 at 4096 tokens, and the
+    small-token stacks (>= 512 MB of distinct packed planes, the batched entry points: one launch pair per operation
+    for the whole stack) of workload 5 at 1, 8 and 16 tokens and workload 3 (q = 1 at 1 token, q = 4 at 8 tokens).
+  * `cpu_baseline`: the CPU oracle timed on a bounded sample of the headline workload.
+A single regime can be run alone with --config / --tokens / --q (and --regimes none).
+
+Roofline figures: `achieved` is the algorithmic work of an operation family (one C-ABI call, all its kernels) divided
+by its HIP-event time; for the large-token regimes the events bracket the calls in the eagerly launched one-stream
+warm-up steps of the same run (the timed region replays a HIP graph over two streams, inside which no event can be
+recorded); for the small-token stacks they bracket the batched calls themselves.  `traffic` is not measured live: it
+is read from the table in profiles/hbm_traffic.md (rocprofv3 --pmc runs of this file's commands) and labelled so.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,34 +33,27 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
-PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # 256 compute units x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
-
-# HBM-side bytes per launch of the dominant kernel of the default workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB copy); see
-# profiles/bench_config2_hbm_traffic.md for the commands and the table.  Not measured live: null for other workloads.
-PMC_TRAFFIC_BYTES = {(2, 4096, 4, "bwd_alpha"): 5.12e7, (2, 4096, 4, "fwd"): 7.76e7, (2, 4096, 4, "bwd_input"): 7.76e7}
-# the same for one whole step of `--config 5 --layer 16384x16384 --tokens 8` per layer copy (fwd 141.2 MB, dalpha 138.6 MB,
-# dx 154.5 MB, the three activation pre-kernels 2.8 MB; profiles/stream_large_layer_kernel_stats.md)
-PMC_TRAFFIC_STREAM_LAYER = {((16384, 16384), 8, 4): 4.252e8}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # a step is about half a millisecond: the defaults time 50 ms of steady state after the clocks have settled
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", type=int, default=2, help="workload number (2 = GPT-2-medium block, the headline)")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, help="headline workload number (4 = OPT-1.3B-shaped block, T = 16384)")
     ap.add_argument("--tokens", type=int, default=0, help="override the token count of the workload")
     ap.add_argument("--q", type=int, default=0, help="override the number of bit planes")
     ap.add_argument("--g", type=int, default=0,
-                    help="group size of the scales along K (Table 4); 0 = row-wise (g = h_in), the headline workload; "
-                         "a layer with K < g uses g = K")
+                    help="group size of the scales along K (Table 4); 0 = row-wise (g = h_in); a layer with K < g uses g = K")
     ap.add_argument("--layer", type=str, default="",
                     help="time ONE layer of shape NxK (e.g. 16384x16384) instead of the workload's four layer shapes; "
                          "seeds, dtype and q still come from --config")
+    ap.add_argument("--regimes", type=str, default="all",
+                    help="'all' (default), 'none', or a comma-separated list of regime names (see REGIMES)")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the two context measurements (device-to-device copy, plain bf16 GEMMs of the same "
                          "shapes through the vendor BLAS that PyTorch links)")
@@ -58,67 +63,79 @@ def parse():
                     help="keep the whole step on one stream.  By default (32 tokens and more) a step is ordered like a "
                          "training step (all forwards, then the backward pass from the last layer) and the scale gradients "
                          "run on a second HIP stream of default priority beside the input gradients, joined at the end "
-                         "of the step: in training dalpha "
-                         "is a leaf of the backward pass (Eq. 4), only the optimizer waits for it")
+                         "of the step: in training dalpha is a leaf of the backward pass (Eq. 4), only the optimizer waits "
+                         "for it")
     ap.add_argument("--no-graph", action="store_true",
-                    help="launch every timed step from Python instead of replaying one captured HIP graph (a step is 32 "
-                         "short launches: on a slow host the Python loop, not the GPU, then sets the pace)")
-    ap.add_argument("--graph", action="store_true", help="accepted for compatibility: graph replay is the default")
+                    help="launch every timed step from Python instead of replaying one captured HIP graph")
+    ap.add_argument("--layer-by-layer", action="store_true",
+                    help="small-token stacks: also time the same stack through the single-layer entry points (one call "
+                         "per layer and operation, captured in one HIP graph)")
     ap.add_argument("--replicas", type=int, default=0,
-                    help="independent copies of the layer stack (own weights), so that the packed planes streamed per "
-                         "step exceed the 256 MB Infinity Cache; default 1, or enough for 512 MB when tokens < 32")
+                    help="small-token stacks: independent copies of the block (own weights); default: enough for 512 MB "
+                         "of packed planes, beyond the 256 MB Infinity Cache")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are part of "
-              "the BCQ linear hot path: rows of W shard without any exchange except one all-reduce of dx)" % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
+# regimes of the default run besides the headline: name -> (kind, config, tokens, q)
+REGIMES = {
+    "config2_T4096": ("large", 2, 4096, 4),
+    "config5_T4096": ("large", 5, 4096, 4),
+    "config5_T8_stack": ("stack", 5, 8, 4),
+    "config5_T1_stack": ("stack", 5, 1, 4),
+    "config5_T16_stack": ("stack", 5, 16, 4),
+    "config3_q1_T1_stack": ("stack", 3, 1, 1),
+    "config3_q4_T8_stack": ("stack", 3, 8, 4),
+}
 
-    import numpy as np
-    import torch
-    import paper_2210_03858_amd as bcq
-    from paper_2210_03858_amd import synth
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    torch.cuda.set_device(0)
-    bcq.load()
+def traffic_from_profile(key):
+    """Bytes per launch from the committed table (lines `| key | fetched bytes | written bytes | ... |`), or None."""
+    try:
+        for line in open(TRAFFIC_TABLE):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 3 and cells[0] == key:
+                return float(cells[1]) + float(cells[2])
+    except (OSError, ValueError):
+        pass
+    return None
 
-    cfg = synth.CONFIGS[args.config]
+
+def timed_events(torch, fn, n):
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(n):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# large-token regime: the four layers of one block through the single-layer entry points
+
+def run_large(args, env, config, T, q, steps, warmup, custom=None, context=True, headline=False):
+    np, torch, bcq, synth = env
+    cfg = synth.CONFIGS[config]
     h = cfg["h"]
-    q = args.q or cfg["q"][-1]
-    T = args.tokens or cfg["tokens"][-1]
     dtype = cfg["dtype"]
     tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
     code = bcq.binding.BCQ_BF16 if dtype == "bf16" else bcq.binding.BCQ_F32
-    kinds = cfg["kinds"]
-    custom = None
-    if args.layer:
-        custom = tuple(int(v) for v in args.layer.lower().split("x"))
-        assert len(custom) == 2 and custom[1] % 32 == 0, "--layer wants NxK with K % 32 == 0"
-        kinds = ("out",)  # seeds of the (h, h) layer
+    kinds = ("out",) if custom else cfg["kinds"]
+    use_graph = not args.no_graph
 
     def shape_of(kind):
         return custom if custom else synth.layer_shape(h, kind)
 
-    small = T < 32            # streaming regime: bound by HBM, measured over a stack of distinct layers
-    use_graph = not args.no_graph
-    block_packed = sum(shape_of(k)[0] * shape_of(k)[1] for k in kinds) * q // 8
-    replicas = args.replicas or (max(1, -(-(512 << 20) // block_packed)) if small else 1)
-
-    # ---------------- one-time setup: synthetic weights -> greedy BCQ on the GPU, twin, activations
+    gen = torch.Generator(device="cuda")
     layers = []
-    setup_ms = {"quantize": 0.0, "pack_transposed": 0.0}
+    setup = {"quantize_ms": 0.0, "pack_transposed_ms": 0.0, "quantize_bytes": 0, "pack_transposed_bytes": 0}
     weights_total = 0
-    for rep, kind in [(r, k) for r in range(replicas) for k in kinds]:
+    for kind in kinds:
         N, K = shape_of(kind)
-        W = torch.from_numpy(synth.weights(args.config, kind, N, K, outliers=cfg["outliers"], extra=rep)).cuda()
+        W = torch.from_numpy(synth.weights(config, kind, N, K, outliers=cfg["outliers"])).cuda()
         g = min(args.g, K) if args.g else K
         e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
         bcq.bcq_quantize_grouped(W, q, g)  # warm
@@ -128,11 +145,16 @@ def main():
         twin = bcq.bcq_pack_transposed(packed) if N % 32 == 0 else None
         e2.record()
         torch.cuda.synchronize()
-        setup_ms["quantize"] += e0.elapsed_time(e1)
-        setup_ms["pack_transposed"] += e1.elapsed_time(e2)
+        setup["quantize_ms"] += e0.elapsed_time(e1)
+        setup["pack_transposed_ms"] += e1.elapsed_time(e2)
+        setup["quantize_bytes"] += 4 * N * K + q * N * K // 8 + 4 * q * N * (K // g)   # W read once, planes + alpha written
+        setup["pack_transposed_bytes"] += 2 * (q * N * K // 8) if twin is not None else 0
         weights_total += N * K
-        x = torch.from_numpy(synth.activations(args.config, kind, T, K, 1, dtype)).cuda().to(tdtype)
-        dy = torch.from_numpy(synth.activations(args.config, kind, T, N, 2, dtype)).cuda().to(tdtype)
+        # activations: seeded, drawn on the GPU (N(0,1) rounded to bf16); the CPU baseline below copies its sample back
+        gen.manual_seed(synth.seed_for(config, kind, 1))
+        x = torch.randn((T, K), generator=gen, device="cuda", dtype=torch.float32).to(tdtype)
+        gen.manual_seed(synth.seed_for(config, kind, 2))
+        dy = torch.randn((T, N), generator=gen, device="cuda", dtype=torch.float32).to(tdtype)
         ws = {}
         for op in (1, 2, 3):
             nbytes = bcq.workspace_bytes_grouped(op, T, N, K, g, q, code)
@@ -156,7 +178,7 @@ def main():
             bcq.bcq_linear_bwd_alpha_grouped(L["packed"], L["x"], L["dy"], L["g"], dalpha=L["da"],
                                              workspace=L["ws"][3])
 
-    side = torch.cuda.Stream() if (not args.no_overlap and not small) else None
+    side = torch.cuda.Stream() if not args.no_overlap else None
 
     def step_overlapped():
         """Ordered like a training step: the forward of every layer first; then, from the last layer back, the input
@@ -172,13 +194,13 @@ def main():
             run_op(L, "bwd_input")
         main.wait_stream(side)
 
-    def step(events=None, only=None):
-        """One pass of the hot path.  With `events`, HIP events bracket every op (or only the ops of family `only`)."""
+    def step(events=None):
+        """One pass of the hot path.  With `events`, HIP events bracket every call (one stream, eager)."""
         if side is not None and events is None:
             return step_overlapped()
         for L in layers:
             for op in ops:
-                if events is not None and (only is None or op == only):
+                if events is not None:
                     a = torch.cuda.Event(enable_timing=True)
                     b = torch.cuda.Event(enable_timing=True)
                     a.record()
@@ -188,18 +210,18 @@ def main():
                 else:
                     run_op(L, op)
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and headline:
         src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    # ---------------- warm-up: every op bracketed by events -> per-op table and the dominant op family
+    # warm-up: every call bracketed by events -> per-op table and the roofline of the dominant op family
     warm_events = []
-    n_warm = max(args.warmup, 2)  # at least two: the per-op figures skip the first step (one-time set-up of the kernels)
+    n_warm = max(warmup, 2)  # at least two: the per-op figures skip the first step (one-time set-up of the kernels)
     for _ in range(n_warm):
-        step(warm_events)
+        step(None if args.no_events else warm_events)
     torch.cuda.synchronize()
     graph = None
     if use_graph:  # the library neither allocates nor memsets, so a step can be captured as it is
@@ -208,34 +230,21 @@ def main():
             step()
         graph.replay()
         torch.cuda.synchronize()
-    # per op family: time per step, median over the warm-up steps but the first (which pays one-time set-up)
-    n_ev = len(ops) * len(layers)
-    fam_steps = {op: [] for op in ops}
-    for i in range(1, n_warm):
-        sums = dict.fromkeys(ops, 0.0)
-        for op, kind, a, b in warm_events[i * n_ev:(i + 1) * n_ev]:
-            sums[op] += a.elapsed_time(b)
-        for op in ops:
-            fam_steps[op].append(sums[op])
-    fam_ms = {op: sorted(v)[(len(v) - 1) // 2] for op, v in fam_steps.items()}  # lower median
-    dom = max(fam_ms, key=lambda k: fam_ms[k])
 
-    # ---------------- timed region: exactly --steps steps; events only around the dominant family's launches
-    # (an event pair costs a few microseconds of GPU idle time, so bracketing all twelve ops would slow the step)
-    events = None if (args.no_events or graph is not None or side is not None) else []
+    # timed region: exactly `steps` steps
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         if graph is not None:
             graph.replay()
         else:
-            step(events, only=dom)
+            step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
 
-    # spread of single steps (not part of `value`): up to 50 more steps, each bracketed by HIP events
+    # spread of single steps (not part of `value`): up to 20 more steps, each bracketed by HIP events
     spread = []
-    for _ in range(min(args.steps, 50)):
+    for _ in range(min(steps, 20)):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         if graph is not None:
@@ -250,147 +259,321 @@ def main():
     flops_layer = {L["kind"]: 2.0 * T * L["N"] * L["K"] for L in layers}
     flops_step = 3.0 * sum(flops_layer.values())
     value = flops_step / (ms_per_step * 1e-3) / 1e12
+    packed_bytes = q * weights_total // 8
 
-    # ---------------- roofline of the dominant op family (timed region) and per-op table (warm-up steps)
-    fam_flops = sum(flops_layer.values())  # every family runs every layer once per step
-    per_op = {op: {"ms_per_step": round(fam_ms[op], 4), "tflops": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12, 3)}
-              for op in ops}
-    roofline = None
-    roofline_note = None
-    if events is None and not small and not args.no_events:
-        # graph replay (no events inside a graph) or two streams (kernels overlap): the per-launch figures come from
-        # the eagerly launched one-stream warm-up steps of this run (all but the first, which pays one-time set-up)
-        events = [e for e in warm_events[len(ops) * len(layers):] if e[0] == dom] or None
-        roofline_note = ("per-launch figures from the %d eagerly launched one-stream warm-up steps of this run; the timed "
-                         "region %s" % (n_warm - 1,
-                                        " and ".join(([("replays a HIP graph of the same step")] if graph is not None else [])
-                                                     + (["runs dalpha on a second stream"] if side is not None else []))))
-    if events:
-        # per step of the dominant family: median over the steps the events cover (robust against a stray slow launch)
-        per_step = len(layers)
-        step_ms = sorted(sum(a.elapsed_time(b) for _, _, a, b in events[i:i + per_step])
-                         for i in range(0, len(events) - per_step + 1, per_step))
-        ms = step_ms[(len(step_ms) - 1) // 2] * (len(events) / per_step)
-        fl = sum(flops_layer[kind] for _, kind, _, _ in events)
-        achieved = fl / (ms * 1e-3) / 1e12
+    per_op, roofline = None, None
+    if warm_events:
+        n_ev = len(ops) * len(layers)
+        fam_steps = {op: [] for op in ops}
+        for i in range(1, n_warm):
+            sums = dict.fromkeys(ops, 0.0)
+            for op, kind, a, b in warm_events[i * n_ev:(i + 1) * n_ev]:
+                sums[op] += a.elapsed_time(b)
+            for op in ops:
+                fam_steps[op].append(sums[op])
+        fam_ms = {op: sorted(v)[(len(v) - 1) // 2] for op, v in fam_steps.items()}  # lower median
+        fam_flops = sum(flops_layer.values())  # every family runs every layer once per step
+        per_op = {op: {"ms_per_step": round(fam_ms[op], 4), "tflops": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12, 3),
+                       "frac_of_peak": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)}
+                  for op in ops}
+        dom = max(fam_ms, key=lambda k: fam_ms[k])
         main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
                        "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
-        if (dom == "fwd" and T <= 80) or (dom == "bwd_input" and T <= 48):  # the library streams the planes up to there
-            main_kernel = "stream_kernel (+ quant_act_kernel), one pass over the planes per 16-token tile"
         bound, peak = "mfma", PEAK_BF16_MFMA_TFLOPS
         if dtype != "bf16":
             # fp32 activations take the any-shape vector-ALU kernels, which execute q plane products (2 q T N K lane
             # operations for 2 T N K effective flops): priced against the fp32 vector peak of the chip
             bound, peak, main_kernel = "alu", PEAK_FP32_VECTOR_TFLOPS, "%s_generic_kernel" % dom
+        achieved = fam_flops / (fam_ms[dom] * 1e-3) / 1e12
+        tkey = "config%d_T%d_q%d_%s" % (config, T, q, dom)
+        traffic = traffic_from_profile(tkey) if not (args.g or custom) else None
         roofline = {"bound": bound, "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
-                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 5),
-                    "traffic": PMC_TRAFFIC_BYTES.get((args.config, T, q, dom)) if not args.g else None,
-                    "avg_launch_us": round(ms * 1e3 / len(events), 2), "launches": len(events),
-                    "algorithmic": "2*T*N*K flops per launch, averaged over the %d layer shapes" % len(layers)}
-        if roofline_note:
-            roofline["note"] = roofline_note
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 5), "traffic": traffic,
+                    "traffic_source": ("profiles/hbm_traffic.md row %s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-scaled; "
+                                       "not measured in this run)" % tkey) if traffic else None,
+                    "avg_launch_us": round(fam_ms[dom] * 1e3 / len(layers), 2), "launches_per_step": len(layers),
+                    "algorithmic": "2*T*N*K flops per call, averaged over the %d layer shapes; the family's helper "
+                                   "kernels are inside the event time" % len(layers),
+                    "note": "HIP events around each call of the slowest operation family in the %d eagerly launched "
+                            "one-stream warm-up steps of this run; per-kernel durations: profiles/" % (n_warm - 1)}
 
-    if small:
-        # streaming regime: the planes are the only large operand; algorithmic bytes of one step
-        sz = 2 if dtype == "bf16" else 4
-        bytes_step = 0.0
-        for L in layers:
-            planes_b = q * L["N"] * L["K"] / 8
-            bytes_step += 3 * planes_b + 2 * 4 * q * L["N"] + 2 * sz * T * (L["K"] + L["N"]) + sz * T * (L["K"] + L["N"])
-        achieved = bytes_step / (ms_per_step * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "stream_kernel / stream_lds_kernel / stream_fused_kernel + quant_act_kernel (fwd, dalpha, dx; whole captured step)",
-                    "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 5),
-                    "traffic": (PMC_TRAFFIC_STREAM_LAYER.get((custom, T, q), 0.0) * replicas or None) if not args.g else None,
-                    "packed_plane_GBps": round(3 * sum(q * L["N"] * L["K"] / 8 for L in layers) / (ms_per_step * 1e-3) / 1e9, 1),
-                    "algorithmic": "per op and layer: q*N*K/8 plane bytes + 4*q*N + activations; planes are read once "
-                                   "by each of fwd, dx, dalpha"}
-
-    # ---------------- context (not a target, not part of the library): what a plain copy and plain bf16 GEMMs of
-    # the same shapes reach on this GPU in this run
-    context = None
-    if not args.no_context and not small and dtype == "bf16":
-        def timed(fn, n=10):
-            fn()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(n):
-                fn()
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) / n
+    ctx = None
+    if context and not args.no_context and dtype == "bf16":
         src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
-        copy_ms = timed(lambda: dst.copy_(src))
+        dst.copy_(src)
+        copy_ms = timed_events(torch, lambda: dst.copy_(src), 5)
         del src, dst
         gemm_ms = 0.0
-        for L in layers[:len(kinds)]:
+        for L in layers:
             Wd = torch.randn((L["N"], L["K"]), dtype=tdtype, device="cuda")
-            gemm_ms += timed(lambda: torch.matmul(L["x"], Wd.t()))          # y  = x  W^T
-            gemm_ms += timed(lambda: torch.matmul(L["dy"], Wd))             # dx = dy W
-            gemm_ms += timed(lambda: torch.matmul(L["dy"].t(), L["x"]))     # dW-shaped product behind dalpha
+            for fn in (lambda: torch.matmul(L["x"], Wd.t()), lambda: torch.matmul(L["dy"], Wd),
+                       lambda: torch.matmul(L["dy"].t(), L["x"])):  # y = x W^T, dx = dy W, dW-shaped product behind dalpha
+                fn()
+                gemm_ms += timed_events(torch, fn, 5)
             del Wd
-        context = {"d2d_copy_GBps": round(2 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1),
-                   "vendor_bf16_gemm_tflops": round(flops_step / replicas / (gemm_ms * 1e-3) / 1e12, 1),
-                   "vendor_bf16_gemm_ms_per_step": round(gemm_ms, 4),
-                   "note": "torch.matmul on dense bf16 weights of the same shapes (3 GEMMs per layer), events around "
-                           "10 back-to-back calls each; read+write bytes for the 1 GiB copy"}
+        ctx = {"d2d_copy_GBps": round(2 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1),
+               "vendor_bf16_gemm_tflops": round(flops_step / (gemm_ms * 1e-3) / 1e12, 1),
+               "vendor_bf16_gemm_ms_per_step": round(gemm_ms, 4),
+               "note": "torch.matmul on dense bf16 weights of the same shapes (3 GEMMs per layer), events around "
+                       "5 back-to-back calls each; read+write bytes for the 1 GiB copy"}
 
-    # ---------------- CPU oracle on a bounded sample of the same workload
+    res = {
+        "workload": "config %d: %s-wide block layers %s, q=%d, %s scales, %s activations, T=%d tokens; fwd+dx+dalpha" % (
+            config, h, ("one %dx%d layer" % custom) if custom else "/".join(kinds), q,
+            ("g=%d group-wise" % args.g) if args.g else "row-wise", dtype, T),
+        "h": h, "q": q, "tokens": T, "g": args.g or "h_in", "weights_per_block": weights_total,
+        "hip_graph": graph is not None, "streams": 2 if side is not None else 1,
+        "order": ("training step: all forwards, then from the last layer back dx on the main stream and dalpha on the "
+                  "second stream, one join") if side is not None else "fwd, dx, dalpha per layer",
+        "steps": steps, "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(spread[len(spread) // 2], 4),
+        "ms_per_step_min": round(spread[0], 4), "tflops": round(value, 3),
+        "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_MFMA_TFLOPS, 4),
+        "packed_weight_bytes": packed_bytes,
+        "packed_weight_GBps": round(3 * packed_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "roofline": roofline, "per_op": per_op, "context": ctx,
+        "setup": {"quantize_ms": round(setup["quantize_ms"], 4),
+                  "quantize_GBps": round(setup["quantize_bytes"] / (setup["quantize_ms"] * 1e-3) / 1e9, 1),
+                  "pack_transposed_ms": round(setup["pack_transposed_ms"], 4),
+                  "pack_transposed_GBps": round(setup["pack_transposed_bytes"] / max(setup["pack_transposed_ms"], 1e-6) / 1e6, 1),
+                  "algorithmic": "quantize: 4NK read + qNK/8 + 4qN written; twin: qNK/8 read + written"},
+    }
+    return res, layers
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# small-token regime: a stack of distinct layers through the batched entry points
+
+def run_stack(args, env, config, T, q, custom=None, iters=20):
+    np, torch, bcq, synth = env
+    cfg = synth.CONFIGS[config]
+    h = cfg["h"]
+    kinds = ("out",) if custom else cfg["kinds"]
+    shapes = [custom if custom else synth.layer_shape(h, k) for k in kinds]
+    block_packed = sum(n * k for n, k in shapes) * q // 8
+    replicas = args.replicas or max(1, -(-(512 << 20) // block_packed))
+    gen = torch.Generator(device="cuda")
+    layers = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for rep in range(replicas):
+        for kind, (N, K) in zip(kinds, shapes):
+            # weights: seeded N(0, 0.02^2) drawn on the GPU (a 512 MB stack at q = 1 is 4.3 G weights), quantized by
+            # the library's greedy quantizer; only the packed planes are kept
+            gen.manual_seed(synth.seed_for(config, kind, 0, rep))
+            W = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+            alpha, packed, _ = bcq.bcq_quantize(W, q)
+            del W
+            twin = bcq.bcq_pack_transposed(packed)
+            gen.manual_seed(synth.seed_for(config, kind, 1, rep))
+            x = torch.randn((T, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            gen.manual_seed(synth.seed_for(config, kind, 2, rep))
+            dy = torch.randn((T, N), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            L = dict(kind=kind, N=N, K=K, alpha=alpha, x=x, dy=dy, tiled=bcq.bcq_pack_decode(packed),
+                     tiled_t=bcq.bcq_pack_decode(twin),
+                     y=torch.empty((T, N), dtype=torch.bfloat16, device="cuda"),
+                     dx=torch.empty((T, K), dtype=torch.bfloat16, device="cuda"),
+                     dalpha=torch.empty((q, N), dtype=torch.float32, device="cuda"))
+            if args.layer_by_layer:
+                L["packed"], L["twin"] = packed, twin
+            layers.append(L)
+            del packed, twin
+    e1.record()
+    torch.cuda.synchronize()
+    setup_ms = e0.elapsed_time(e1)
+
+    names = {1: "fwd", 2: "bwd_input", 3: "bwd_alpha"}
+    plans = {op: bcq.batch_plan(op, layers, T, q) for op in (1, 2, 3)}
+    for _ in range(3):
+        for op in (1, 2, 3):
+            bcq.bcq_linear_batched(plans[op])
+    torch.cuda.synchronize()
+    op_ms = {names[op]: timed_events(torch, lambda: bcq.bcq_linear_batched(plans[op]), iters) for op in (1, 2, 3)}
+
+    def step():
+        for op in (1, 2, 3):
+            bcq.bcq_linear_batched(plans[op])
+    t0 = time.perf_counter()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / iters
+
+    planes = sum(q * L["N"] * L["K"] // 8 for L in layers)
+    # algorithmic bytes of one operation over the stack: planes + scales or their gradient + the two activations
+    other = {"fwd": sum(4 * q * L["N"] + 2 * T * (L["K"] + L["N"]) for L in layers),
+             "bwd_input": sum(4 * q * L["N"] + 2 * T * (L["K"] + L["N"]) for L in layers),
+             "bwd_alpha": sum(4 * q * L["N"] + 2 * T * (L["K"] + L["N"]) for L in layers)}
+    per_op = {}
+    for name, ms in op_ms.items():
+        tot = planes + other[name]
+        per_op[name] = {"ms": round(ms, 4), "packed_weight_GBps": round(planes / (ms * 1e-3) / 1e9, 1),
+                        "total_GBps": round(tot / (ms * 1e-3) / 1e9, 1),
+                        "frac_of_hbm_peak": round(tot / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    dom = max(op_ms, key=lambda k: op_ms[k])
+    tot_dom = planes + other[dom]
+    tkey = "config%d_T%d_q%d_stack_%s" % (config, T, q, dom)
+    traffic = traffic_from_profile(tkey) if not custom else None
+    roofline = {"bound": "hbm", "kernel": "stream_tile_batched_kernel (+ quant_act_batched_kernel)",
+                "op": "bcq_linear_batched " + dom, "achieved": round(tot_dom / (op_ms[dom] * 1e-3) / 1e9, 1),
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(tot_dom / (op_ms[dom] * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
+                "traffic": traffic,
+                "traffic_source": ("profiles/hbm_traffic.md row %s (not measured in this run)" % tkey) if traffic else None,
+                "avg_launch_us": round(op_ms[dom] * 1e3, 2), "launches_per_step": 1,
+                "algorithmic": "per call over the stack: q*N*K/8 plane bytes + 4*q*N + 2*T*(K+N) per layer",
+                "note": "HIP events around %d back-to-back batched calls of the slowest operation (pre-kernel + main "
+                        "kernel); the planes are read once by each of fwd, dx, dalpha" % iters}
+    flops_step = 6.0 * T * sum(L["N"] * L["K"] for L in layers)
+    res = {
+        "workload": "config %d: stack of %d x (%s) layers of width %d (%d layers, %.1f MB of packed planes), q=%d, row-wise "
+                    "scales, bf16 activations, T=%d tokens; fwd+dx+dalpha through the batched entry points (one launch pair "
+                    "per operation)" % (config, replicas, ("%dx%d" % custom) if custom else "/".join(kinds), h, len(layers),
+                                        planes / 1e6, q, T),
+        "h": h, "q": q, "tokens": T, "layers": len(layers), "layer_stack_replicas": replicas,
+        "ms_per_step": round(ms_per_step, 4), "tflops": round(flops_step / (ms_per_step * 1e-3) / 1e12, 3),
+        "packed_weight_bytes": planes,
+        "packed_weight_GBps": round(3 * planes / (ms_per_step * 1e-3) / 1e9, 1),
+        "frac_of_hbm_peak": round(3 * planes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "roofline": roofline, "per_op": per_op,
+        "setup": {"stack_ms": round(setup_ms, 2), "note": "random weights, greedy quantizer, twin and two decode layouts "
+                                                           "per layer, launched from Python"},
+    }
+    if args.layer_by_layer:
+        ws = {}
+        for L in layers:
+            L["ws"] = {op: torch.empty((max(bcq.workspace_bytes(op, T, L["N"], L["K"], q, 1), 16),), dtype=torch.uint8,
+                                       device="cuda") for op in (1, 2, 3)}
+
+        def lbl():
+            for L in layers:
+                bcq.bcq_linear_fwd(L["packed"], L["alpha"], L["x"], y=L["y"], workspace=L["ws"][1])
+                bcq.bcq_linear_bwd_input(L["packed"], L["alpha"], L["dy"], packed_t=L["twin"], dx=L["dx"], workspace=L["ws"][2])
+                bcq.bcq_linear_bwd_alpha(L["packed"], L["x"], L["dy"], dalpha=L["dalpha"], workspace=L["ws"][3])
+        lbl()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lbl()
+        graph.replay()
+        ms = timed_events(torch, graph.replay, 10)
+        res["layer_by_layer"] = {"ms_per_step": round(ms, 4), "packed_weight_GBps": round(3 * planes / (ms * 1e-3) / 1e9, 1),
+                                 "note": "single-layer entry points, %d calls in one HIP graph" % (3 * len(layers))}
+    del plans, layers
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(env, config, T, q, layers, g_arg):
+    """The oracle as it stands on a bounded token slice of the same layers and activations."""
+    np, torch, bcq, synth = env
+    from oracle import bcq_oracle as oracle
+    cfg = synth.CONFIGS[config]
+    total_nk = sum(L["N"] * L["K"] for L in layers)
+    Ts = T
+    while Ts > 1 and 6.0 * Ts * total_nk > 1.6e11:  # about 10 - 15 s of naive fp64 loops on 16 cores
+        Ts //= 2
+    spent, flops_done, done = 0.0, 0.0, []
+    for L in layers:
+        N, K = L["N"], L["K"]
+        W = synth.weights(config, L["kind"], N, K, outliers=cfg["outliers"])
+        gl = min(g_arg, K) if g_arg else K
+        a_ref, planes_ref = oracle.quantize(W, q, g=gl)
+        xs = L["x"][:Ts].float().cpu().numpy()
+        dys = L["dy"][:Ts].float().cpu().numpy()
+        c0 = time.perf_counter()
+        oracle.fwd(a_ref, planes_ref, xs)
+        oracle.bwd_input(a_ref, planes_ref, dys)
+        oracle.bwd_alpha(planes_ref, xs, dys, g=gl)
+        spent += time.perf_counter() - c0
+        flops_done += 6.0 * Ts * N * K
+        done.append("%s %dx%d" % (L["kind"], N, K))
+    return {"value": round(flops_done / spent / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(spent, 2),
+            "sample": "fwd+dx+dalpha on the first %d of the %d tokens, q=%d, fp64 naive loops, all layers: %s" % (
+                Ts, T, q, "; ".join(done))}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives are part of "
+              "the BCQ linear hot path: rows of W shard without any exchange except one all-reduce of dx)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2210_03858_amd as bcq
+    from paper_2210_03858_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    bcq.load()
+    env = (np, torch, bcq, synth)
+
+    cfg = synth.CONFIGS[args.config]
+    q = args.q or cfg["q"][-1]
+    T = args.tokens or cfg["tokens"][-1]
+    custom = None
+    if args.layer:
+        custom = tuple(int(v) for v in args.layer.lower().split("x"))
+        assert len(custom) == 2 and custom[1] % 32 == 0, "--layer wants NxK with K % 32 == 0"
+
+    small = T <= 16 and cfg["dtype"] == "bf16" and not args.g
     cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import bcq_oracle as oracle
-        budget_s, spent, flops_done, done = 12.0, 0.0, 0.0, []
-        for kind in sorted(kinds, key=lambda k: shape_of(k)[0] * shape_of(k)[1]):
-            if spent > budget_s:
-                break
-            N, K = shape_of(kind)
-            W = synth.weights(args.config, kind, N, K, outliers=cfg["outliers"])
-            gl = min(args.g, K) if args.g else K
-            a_ref, planes_ref = oracle.quantize(W, q, g=gl)
-            Ts = min(T, 4096)
-            xs = synth.activations(args.config, kind, T, K, 1, dtype)[:Ts]
-            dys = synth.activations(args.config, kind, T, N, 2, dtype)[:Ts]
-            c0 = time.perf_counter()
-            oracle.fwd(a_ref, planes_ref, xs)
-            oracle.bwd_input(a_ref, planes_ref, dys)
-            oracle.bwd_alpha(planes_ref, xs, dys, g=gl)
-            spent += time.perf_counter() - c0
-            flops_done += 6.0 * Ts * N * K
-            done.append("%s %dx%d x %d tokens" % (kind, N, K, Ts))
-        cpu = {"value": round(flops_done / spent / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "seconds": round(spent, 2),
-               "sample": "fwd+dx+dalpha, q=%d, fp64 naive loops, layers: %s" % (q, "; ".join(done))}
+    if small:
+        head = run_stack(args, env, args.config, T, q, custom=custom, iters=max(args.steps, 1))
+        value, unit, metric = head["packed_weight_GBps"], "GB/s", "BCQ linear fwd+bwd packed-weight GB/s"
+    else:
+        head, layers = run_large(args, env, args.config, T, q, args.steps, args.warmup, custom=custom, headline=True)
+        value, unit, metric = head["tflops"], "TFLOP/s", "BCQ linear fwd+bwd effective TFLOP/s"
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline(env, args.config, T, q, layers, args.g)
+        del layers
+        torch.cuda.empty_cache()
+
+    regimes = {}
+    wanted = [] if args.regimes == "none" else (list(REGIMES) if args.regimes == "all" else args.regimes.split(","))
+    if args.regimes == "all" and (args.tokens or args.q or args.g or args.layer or args.config != 4):
+        wanted = []  # a single regime was asked for
+    for name in wanted:
+        kind, c, t, qq = REGIMES[name]
+        if kind == "large":
+            if (c, t, qq) == (args.config, T, q):
+                continue
+            r, _ = run_large(args, env, c, t, qq, min(args.steps, 20), min(max(args.warmup, 3), 5), context=True)
+            del _
+        else:
+            r = run_stack(args, env, c, t, qq)
+        torch.cuda.empty_cache()
+        regimes[name] = r
 
     out = {
-        "metric": "BCQ linear fwd+bwd effective TFLOP/s",
-        "value": round(value, 3),
-        "unit": "TFLOP/s",
+        "metric": metric,
+        "value": value,
+        "unit": unit,
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
-        "ms_per_step_median": round(spread[len(spread) // 2], 4),
-        "ms_per_step_min": round(spread[0], 4),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": dtype,
+        "dtype": cfg["dtype"],
         "data": "synthetic",
-        "config": {"workload": "config %d: %s-wide block layers %s, q=%d, %s scales, %s activations, T=%d tokens; "
-                               "fwd+dx+dalpha" % (args.config, h, ("one %dx%d layer" % custom) if custom else "/".join(kinds), q,
-                                                  ("g=%d group-wise" % args.g) if args.g else "row-wise", dtype, T),
-                   "h": h, "q": q, "tokens": T, "g": args.g or "h_in", "weights_per_block": weights_total // replicas,
-                   "layer_stack_replicas": replicas, "hip_graph": graph is not None,
-                   "streams": 2 if side is not None else 1,
-                   "order": ("training step: all forwards, then from the last layer back dx on the main stream and "
-                             "dalpha on the second stream, one join") if side is not None else "fwd, dx, dalpha per layer"},
-        "roofline": roofline,
+        "config": {k: head[k] for k in head if k not in ("roofline", "per_op", "context", "setup", "ms_per_step", "tflops")},
+        "packed_weight_GBps": head["packed_weight_GBps"],
+        "roofline": head["roofline"],
         "cpu_baseline": cpu,
-        "context": context,
-        "per_op": per_op,
-        "setup": {k: round(v, 4) for k, v in setup_ms.items()},
-        "packed_weight_bytes": q * weights_total // 8,
+        "context": head.get("context"),
+        "per_op": head["per_op"],
+        "setup": head["setup"],
+        "regimes": regimes,
+        "targets": {"large_token": ">= 0.50 of the bf16 MFMA peak at >= 2048 tokens", "small_token": ">= 0.70 of the HBM peak "
+                    "at <= 8 tokens", "status": "both open: see roofline.frac of the headline and of the regimes"},
     }
     print(json.dumps(out))
 
