@@ -36,6 +36,16 @@
  *   - Limits: 1 <= q <= 8; K % 32 == 0; 1 <= N, K <= 2^17; 1 <= T <= 2^24; N*K and T*max(N,K) at most 2^40.
  *   - No global state besides per-device capability caches; calls on different streams may overlap
  *     as long as their outputs and workspaces do not alias.
+ *   - Numerics of the bf16 paths (fp32 accumulation throughout; the bar of the tests is 2e-2 of the largest output):
+ *     the matrix-core path (32 tokens and more, workspace given) first sums the planes into What = sum_i alpha_i B_i
+ *     and rounds What to bf16 once (relative 2^-9 per weight) - a rounding Eq. 2 / Eq. 3 do not contain; alpha itself
+ *     stays fp32.  The streaming paths (few tokens) multiply exact signs with activations split into two FP8 terms:
+ *     exact for bf16 activations within 2^-13 of the largest of their 32-element block (forward, scale gradient); the
+ *     input gradient re-codes the fp32 product dy * alpha_i and keeps 8 significant bits of it (relative 2^-9 per
+ *     term).  Without a workspace, and for fp32 activations, no such rounding happens.
+ *   - Non-finite activations: a token row of x or dy that holds an Inf or NaN makes the outputs of that token
+ *     non-finite and leaves every other token's outputs untouched (the scale gradient sums over tokens and becomes
+ *     non-finite as a whole); the streaming paths return NaN for every output of such a token.
  *   - HIP graphs: every call only launches kernels on `stream` (no allocation, no memset, no
  *     synchronisation), so it can be recorded into a graph.  The first launch of a kernel that
  *     needs more than 64 KiB of LDS raises that kernel's limit (a host-side attribute call), so

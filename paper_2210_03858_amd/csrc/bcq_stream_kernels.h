@@ -10,8 +10,13 @@
 //     (nibble jj of reg_s carries bit 4 jj + 3 - s of the word) - 8 vector-ALU operations per 32 weights.
 //   * The activations are the other operand as FP8 (e4m3) with a power-of-two scale per 32 contraction indices
 //     (hardware block scaling).  A bf16 value has 8 significant bits = two e4m3 terms of 4 bits each, so
-//     x = s (f1 + f2 / 16) EXACTLY for every element within 2^-13 of its block's maximum (smaller elements keep an
-//     absolute error below 2^-21 of that maximum).  A short pre-kernel writes the two terms, already in the
+//     x = s (f1 + f2 / 16) EXACTLY for every bf16 element within 2^-13 of its block's maximum (smaller elements keep
+//     an absolute error below 2^-21 of that maximum).  That holds for the forward and the scale gradient, whose
+//     re-coded operand is a bf16 activation.  The input gradient re-codes the fp32 product dy * alpha_i: two FP8 terms
+//     keep 8 of its 24 significant bits, i.e. every term of Eq. 3 carries a relative error of up to 2^-9, the same
+//     size as rounding alpha_i * dy to bf16 (and as the bf16 weight sums of the matrix-core path).  A block that holds
+//     an Inf or a NaN is given the NaN scale byte, so a non-finite activation turns exactly its own token's outputs
+//     into NaN.  A short pre-kernel writes the two terms, already in the
 //     register order of the instruction and with the contraction index permuted to match the sign expansion
 //     above.  With at most 8 tokens both terms sit side by side in the 16 columns of ONE instruction
 //     (column t and t + 8), else they take two instructions.
@@ -67,20 +72,29 @@ __device__ __forceinline__ uint32_t q_pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ void recode_unit(const float (&v)[32], int tl, int G, int j, bool one_half, unsigned char* xb,
                                             unsigned char* sb) {
     float amax = 0.f;
+    bool finite = true;
 #pragma unroll
-    for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
+    for (int e = 0; e < 32; ++e) {
+        amax = fmaxf(amax, fabsf(v[e]));
+        finite = finite && (fabsf(v[e]) <= 3.0e38f);  // false for Inf and NaN
+    }
     // smallest power of two 2^E with amax / 2^E <= 448 (largest e4m3 value = 1.75 * 2^8); scale byte = E + 127
     int sb1 = 127;
-    if (amax > 0.f && amax <= 3.0e38f) {
+    if (amax > 0.f && finite) {
         const uint32_t u = __float_as_uint(amax);
         const int e = (int)(u >> 23) - 127;
         const int E = ((u & 0x7FFFFFu) <= 0x600000u) ? e - 8 : e - 7;
         sb1 = E + 127;
         sb1 = sb1 < 0 ? 0 : sb1;
     }
-    const int sb2 = sb1 >= 4 ? sb1 - 4 : 0;                       // second term: 1/16 of the first scale
+    int sb2 = sb1 >= 4 ? sb1 - 4 : 0;                             // second term: 1/16 of the first scale
     const float inv1 = __uint_as_float((uint32_t)(254 - sb1) << 23); // 2^-(sb1 - 127); sb1 <= 247, so it is normal
     const float up2 = __uint_as_float((uint32_t)(127 + sb1 - sb2) << 23);
+    // A block that holds an Inf or a NaN gets the NaN scale byte (0xFF) for both terms: every product of the block, and
+    // with it every output of this token that contracts over the block, becomes NaN.  A non-finite activation so shows
+    // in its own token's outputs and in no other token's (tokens are separate columns of the instruction, each with
+    // scale bytes of its own).
+    const int sbw1 = finite ? sb1 : 255, sbw2 = finite ? sb2 : 255;
     // element kappa' = 8 s + jj of the block is bit (column) 4 jj + 3 - s of the word
     uint32_t t1[8], t2[8];
 #pragma unroll
@@ -111,8 +125,8 @@ __device__ __forceinline__ void recode_unit(const float (&v)[32], int tl, int G,
         *reinterpret_cast<q_u32x4*>(xb + hh * (QBLK / 2) + (gB * 16 + col1) * 16) = o1;
         *reinterpret_cast<q_u32x4*>(xb + half2 * QBLK + hh * (QBLK / 2) + (gB * 16 + col2) * 16) = o2;
     }
-    sb[(col1 + 16 * G) * 4 + j] = (unsigned char)sb1;
-    sb[half2 * QSCL + (col2 + 16 * G) * 4 + j] = (unsigned char)sb2;
+    sb[(col1 + 16 * G) * 4 + j] = (unsigned char)sbw1;
+    sb[half2 * QSCL + (col2 + 16 * G) * 4 + j] = (unsigned char)sbw2;
 }
 
 // 32 bf16 values -> fp32

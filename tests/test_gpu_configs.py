@@ -222,3 +222,32 @@ def test_step_as_hip_graph_with_second_stream_matches_eager(bcq, oracle, T):
     y_ref = oracle.fwd_at(L["a_ref"], L["planes_ref"], x_h, ts, ns)
     scale = np.abs(y_ref).max()
     assert np.abs(L["ye"].float().cpu().numpy()[ts, ns] - y_ref).max() / scale <= tol_for("bf16")
+
+
+# ------------------------------------------------------------------ every (q, kind, T) cell of workloads 3, 4 and 5
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4])
+@pytest.mark.parametrize("kind", synth.LAYER_KINDS)
+def test_config3_training_regime_every_cell(bcq, oracle, q, kind):
+    """d = 1280 at 4 x 1024 tokens: all 16 (q, layer kind) cells on sampled outputs."""
+    _sampled_layer(bcq, oracle, 3, kind, 4 * 1024, q, "bf16", seed=40 + 4 * q + synth.LAYER_KINDS.index(kind))
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4])
+@pytest.mark.parametrize("T", [1, 4, 8])
+def test_config3_decode_regime_other_kinds(bcq, oracle, q, T):
+    """The two layer kinds test_config3_decode_regime leaves out, compared in full."""
+    for kind in ("out", "mlp_up"):
+        _sampled_layer(bcq, oracle, 3, kind, T, q, "bf16", full=True)
+
+
+def test_config4_opt13b_outlier_rows_qkv(bcq, oracle):
+    _sampled_layer(bcq, oracle, 4, "qkv", 8 * 2048, 3, "bf16", outliers=True, seed=21)
+
+
+@pytest.mark.parametrize("T", [1, 16, 256, 4096])
+@pytest.mark.parametrize("kind", synth.LAYER_KINDS)
+def test_config5_every_kind_at_every_token_count(bcq, oracle, kind, T):
+    """d = 2560, q = 4: all four layer kinds at 1, 16 (in full), 256 and 4096 tokens (sampled).  At 1 and 16 tokens the
+    2560 x 10240 layer takes the shared-activation streaming kernel for its input gradient."""
+    _sampled_layer(bcq, oracle, 5, kind, T, 4, "bf16", full=(T <= 16), seed=60 + T + synth.LAYER_KINDS.index(kind))

@@ -569,3 +569,57 @@ def test_adamw_step_matches_torch_optimizer(oracle):
     g = np.array([0.5, -2.0])
     a1, _, _ = oracle.adamw_step(np.array([1.0, 1.0]), g, np.zeros(2), np.zeros(2), 1, 0.1, 0.9, 0.999, 0.0, 0.5)
     assert np.allclose(a1, 1.0 - 0.1 * (np.sign(g) + 0.5), rtol=1e-14)
+
+
+# ------------------------------------------------------------------ the oracle's fragility reporters
+# They decide which rows / vectors a GPU parity test may excuse from bit-exactness, so they get pins of their own.
+
+def test_round_margin_on_hand_built_means(oracle):
+    """margin = distance of the fp64 mean |w| to the nearer fp32 rounding boundary, relative to the mean.
+    Rows whose mean is known exactly: on an fp32 value (half an ulp away from either boundary; a power of two has the
+    nearer boundary a quarter of the upper ulp below), exactly on a boundary (0), and an eighth of an ulp above a value."""
+    u = 2.0 ** -23  # ulp of fp32 values in [1, 2)
+    rows = np.zeros((5, 32), np.float32)
+    rows[0, :] = 1.5                       # mean 1.5: boundaries at 1.5 -+ u/2
+    rows[0, ::2] *= -1
+    rows[1, :] = 1.0                       # mean 1.0: lower boundary at 1 - u/4 (the ulp halves below a power of two)
+    rows[2, :16], rows[2, 16:] = 1.5, np.float32(1.5 + u)      # mean 1.5 + u/2: exactly the boundary
+    rows[3, :28], rows[3, 28:] = 1.5, np.float32(1.5 + u)      # mean 1.5 + u/8
+    rows[4, :] = 0.0                       # mean 0: reported as robust (alpha = 0 whatever the order of the sum)
+    _, _, margin = oracle.quantize(rows, 1, with_margin=True)
+    assert margin.shape == (1, 5)
+    assert margin[0, 0] == (u / 2) / 1.5
+    assert margin[0, 1] == (u / 4) / 1.0
+    assert margin[0, 2] == 0.0
+    assert margin[0, 3] == (u / 2 - u / 8) / (1.5 + u / 8)
+    assert margin[0, 4] == 1.0
+    # with more planes every plane reports its own mean: plane 2 of row 0 has residual 0 everywhere
+    _, _, m2 = oracle.quantize(rows[:1], 2, with_margin=True)
+    assert m2[0, 0] == (u / 2) / 1.5 and m2[1, 0] == 1.0
+
+
+def test_alternating_decision_gap_on_a_hand_built_vector(oracle):
+    """margin[:, 0] = smallest (distance to the second nearest level - distance to the nearest), over all elements and
+    rounds, relative to sum |alpha|.  q = 1, sixteen +1, fifteen -1 and one +0.25: alpha = 31.25 / 32 in every round; the
+    +-1 elements have gap 2 alpha, the 0.25 element has gap 0.5, so the reported margin is 0.5 / alpha exactly.  An
+    element that is exactly 0 ties between the mirror levels +-alpha; that tie is resolved by rule, not by rounding, and
+    must not be reported as a gap of 0."""
+    w = np.array([1.0] * 16 + [-1.0] * 15 + [0.25], np.float32)[None, :]
+    alpha, planes, margin, done = oracle.quantize_alternating(w, 1, iters=15, with_margin=True)
+    a = 31.25 / 32
+    assert alpha[0, 0] == np.float32(a) and done[0] == 1          # the greedy pair is already the fixed point
+    # (the refit goes through a Cholesky factor, so the fp64 alpha carries a rounding or two: relative 1e-15)
+    assert abs(margin[0, 0] - 0.5 / a) <= 1e-15
+    assert abs(margin[0, 1] - (2.0 ** -24 / 2) / a) <= 1e-12      # a is an fp32 value in [0.5, 1): half of its ulp 2^-24
+    w0 = w.copy()
+    w0[0, 31] = 0.0                                                # mirror tie at an exact zero
+    alpha, planes, margin, done = oracle.quantize_alternating(w0, 1, iters=15, with_margin=True)
+    a0 = 31.0 / 32
+    assert alpha[0, 0] == np.float32(a0) and planes[0, 0, 31] == 1  # tie -> the larger level
+    assert margin[0, 0] == 1.0        # only the +-1 elements count: gap 2 alpha / alpha = 2, reported capped at 1
+    # q = 2 on a vector with two exact magnitudes: levels +-(a1 +- a2) = +-3, +-1; every element sits on a level, the
+    # nearest other level is 2 away: gap 2 / (a1 + a2) = 2 / 3
+    w2 = np.array([3.0, -3.0, 1.0, -1.0] * 8, np.float32)[None, :]
+    alpha, planes, margin, done = oracle.quantize_alternating(w2, 2, iters=15, with_margin=True)
+    assert sorted(np.abs(alpha[:, 0]).tolist()) == [1.0, 2.0]
+    assert abs(margin[0, 0] - 2.0 / 3.0) <= 1e-15
