@@ -49,7 +49,7 @@
  *   - HIP graphs: every call only launches kernels on `stream` (no allocation, no memset, no
  *     synchronisation), so it can be recorded into a graph.  The first launch of a kernel that
  *     needs more than 64 KiB of LDS raises that kernel's limit (a host-side attribute call), so
- *     run each call once with its shapes before the capture.  A captured call keeps pointing at
+ *     run each call once with its shapes before the capture, or call bcq_prepare / bcq_batch_prepare.  A captured call keeps pointing at
  *     the buffers it was recorded with.
  */
 #ifndef BCQ_H
@@ -92,7 +92,7 @@ const char* bcq_status_string(bcq_status s);
 
 /* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points;
  * 5: decode layout; 6: bcq_linear_fwd_static;
- * 7: batched small-token calls). */
+ * 7: batched small-token calls; 8: bcq_prepare, bcq_batch_prepare). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -102,6 +102,14 @@ bcq_status bcq_workspace_bytes(int op, int64_t T, int64_t N, int64_t K, int q, i
 /* bcq_workspace_bytes for group size g. */
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out);
+
+/* Host-side one-time set-up for later calls of `op` (BCQ_OP_*) with these arguments, with or without a workspace and
+ * twin and for every q_train: the kernels those calls select get their dynamic-LDS limit raised where they need more
+ * than 64 KiB, and bcq_linear_fwd_static's scratch address is looked up.  Nothing is launched, allocated or read.
+ * After it the calls only launch kernels, so the very first one may already sit inside a HIP graph capture.
+ * Not needed otherwise: every entry point does the same set-up by itself on first use.
+ * g = K for row-wise scales.  Errors: BCQ_ERR_DTYPE (op, dtype), BCQ_ERR_SHAPE, BCQ_ERR_DEVICE. */
+bcq_status bcq_prepare(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype);
 
 /* Greedy BCQ quantizer (Appendix C: Eq. ap1 for the first plane, Eq. ap2-ap3 for the others).
  * Per row n: r = W[n][:] in fp64; for i = 0..q-1: B_i = (r >= 0 ? +1 : -1) (so sign(0) = +1),
@@ -290,6 +298,10 @@ bcq_status bcq_batch_plan(int op, const bcq_batch_layer* layers, int64_t count, 
  * BCQ_ERR_DTYPE if table_host does not hold a plan of this library version. */
 bcq_status bcq_linear_batched(const void* table_host, const void* table_device, size_t table_bytes, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/* Host-side one-time set-up of bcq_linear_batched for this plan (see bcq_prepare): after it, the first
+ * bcq_linear_batched with the plan only launches kernels and may sit inside a HIP graph capture. */
+bcq_status bcq_batch_prepare(const void* table_host, size_t table_bytes);
 
 /* One AdamW step (Appendix A: AdamW with a linear-decay learning rate, the schedule being the caller's: pass the
  * step's lr).  Decoupled weight decay, bias-corrected moments, t = step >= 1:

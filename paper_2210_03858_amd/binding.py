@@ -22,7 +22,8 @@ EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_q
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
            "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
            "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw", "bcq_decode_layout_bytes", "bcq_pack_decode",
-           "bcq_linear_fwd_decode", "bcq_linear_fwd_static", "bcq_batch_sizes", "bcq_batch_plan", "bcq_linear_batched")
+           "bcq_linear_fwd_decode", "bcq_linear_fwd_static", "bcq_batch_sizes", "bcq_batch_plan", "bcq_linear_batched",
+           "bcq_prepare", "bcq_batch_prepare")
 
 _lib = None
 
@@ -85,6 +86,8 @@ def load():
     lib.bcq_batch_sizes.argtypes = [i32, bl, i64, i64, i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.bcq_batch_plan.argtypes = [i32, bl, i64, i64, i32, i32, f32, i32, vp, sz]
     lib.bcq_linear_batched.argtypes = [vp, vp, sz, vp, sz, vp]
+    lib.bcq_prepare.argtypes = [i32, i64, i64, i64, i64, i32, i32]
+    lib.bcq_batch_prepare.argtypes = [vp, sz]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = i32
     _lib = lib
@@ -500,3 +503,14 @@ def bcq_linear_batched(plan):
     wp, wbytes = _ws(plan.workspace)
     _check(load().bcq_linear_batched(ctypes.c_void_p(plan.table_host.data_ptr()), _ptr(plan.table_dev),
                                      plan.table_host.numel(), wp, wbytes, _stream()), "bcq_linear_batched")
+
+
+def bcq_batch_prepare(plan):
+    """Host-side set-up of bcq_linear_batched for this plan (before a first call inside a graph capture)."""
+    _check(load().bcq_batch_prepare(ctypes.c_void_p(plan.table_host.data_ptr()), plan.table_host.numel()),
+           "bcq_batch_prepare")
+
+
+def bcq_prepare(op, T, N, K, q, dtype=BCQ_BF16, g=None):
+    """Host-side set-up for later calls of `op` with these shapes (before a first call inside a graph capture)."""
+    _check(load().bcq_prepare(op, T, N, K, K if g is None else int(g), q, dtype), "bcq_prepare")

@@ -184,7 +184,7 @@ __global__ void alt_zero_word_kernel(int* p) { *p = 0; }
 hipError_t launch_quantize_alternating(const float* W, int64_t V, int64_t n, int q, int iters, float* alpha,
                                        uint32_t* packed, int8_t* planes, int* status_word, hipStream_t st) {
     if (status_word) {
-        hipLaunchKernelGGL(alt_zero_word_kernel, dim3(1), dim3(1), 0, st, status_word);
+        BCQ_LAUNCH(alt_zero_word_kernel, dim3(1), dim3(1), 0, st, status_word);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -192,7 +192,7 @@ hipError_t launch_quantize_alternating(const float* W, int64_t V, int64_t n, int
     static LdsLimit limit;
     hipError_t ea = limit.ensure((const void*)alternating_kernel, lds);
     if (ea != hipSuccess) return ea;
-    hipLaunchKernelGGL(alternating_kernel, dim3((unsigned)V), dim3(ALT_THREADS), lds, st, W, V, (int)n, q, iters, alpha,
+    BCQ_LAUNCH(alternating_kernel, dim3((unsigned)V), dim3(ALT_THREADS), lds, st, W, V, (int)n, q, iters, alpha,
                        packed, planes, status_word);
     return hipGetLastError();
 }

@@ -8,6 +8,8 @@
 
 #include <atomic>
 
+thread_local bool bcq::tl_dry_run = false;
+
 // One capability probe per device, cached: 0 = unknown, 1 = gfx950, 2 = anything else.  Racing first calls store
 // the same value.
 bool bcq::host::device_ok() {
@@ -133,7 +135,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 7; }
+int bcq_abi_version(void) { return 8; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {
@@ -443,3 +445,54 @@ bcq_status bcq_linear_bwd_alpha(const uint32_t* packed, const void* x, const voi
 }
 
 }  // extern "C"
+
+namespace {
+struct DryRun {  // sets the calling thread's dry-run flag for the lifetime of the object
+    DryRun() { bcq::tl_dry_run = true; }
+    ~DryRun() { bcq::tl_dry_run = false; }
+};
+}  // namespace
+
+extern "C" bcq_status bcq_prepare(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype) {
+    if (op < BCQ_OP_QUANTIZE || op > BCQ_OP_BWD_ALPHA) return BCQ_ERR_DTYPE;
+    if (op == BCQ_OP_QUANTIZE) T = 1;
+    bcq_status s = check_shape(T, N, K, q);
+    if (s != BCQ_OK) return s;
+    s = check_group(K, g);
+    if (s != BCQ_OK) return s;
+    if (dtype != BCQ_F32 && dtype != BCQ_BF16) return BCQ_ERR_DTYPE;
+    s = check_device();
+    if (s != BCQ_OK) return s;
+    // Stand-in pointers: aligned, never dereferenced (no kernel is launched in a dry run).
+    void* const p = reinterpret_cast<void*>((uintptr_t)1 << 20);
+    const uint32_t* pu = static_cast<const uint32_t*>(p);
+    float* pf = static_cast<float*>(p);
+    const size_t ws = workspace_need(op, T, N, K, g, q, dtype);
+    DryRun guard;
+    const bool twin_ok = (N % 32 == 0);
+    for (int with_ws = 0; with_ws < 2 && s == BCQ_OK; ++with_ws) {
+        void* w = with_ws ? p : nullptr;
+        const size_t wb = with_ws ? (ws > 16 ? ws : 16) : 0;
+        switch (op) {
+            case BCQ_OP_QUANTIZE:
+                if (g <= BCQ_QUANTIZE_MAX_K) s = bcq_quantize_grouped(pf, N, K, g, q, pf, static_cast<uint32_t*>(p), nullptr, w, wb, nullptr);
+                break;
+            case BCQ_OP_FWD:
+                s = bcq_linear_fwd_grouped(pu, pf, p, dtype, T, N, K, g, q, p, w, wb, nullptr);
+                if (s == BCQ_OK && with_ws && g == K && dtype == BCQ_BF16 && T <= BCQ_STATIC_MAX_TOKENS &&
+                    bcq::stream_fwd_workspace(T, K) <= (size_t)BCQ_STATIC_SCRATCH_BYTES)
+                    s = bcq_linear_fwd_static(pu, pf, p, dtype, T, N, K, q, p, nullptr);
+                break;
+            case BCQ_OP_BWD_INPUT:
+                s = bcq_linear_bwd_input_grouped(pu, nullptr, pf, p, dtype, T, N, K, g, q, p, w, wb, nullptr);
+                if (s == BCQ_OK && twin_ok) s = bcq_linear_bwd_input_grouped(pu, pu, pf, p, dtype, T, N, K, g, q, p, w, wb, nullptr);
+                break;
+            default:
+                for (int qt = 1; qt <= q && s == BCQ_OK; ++qt)  // the kernels are specialised by the number of trained planes
+                    s = bcq_linear_bwd_alpha_grouped(pu, p, p, dtype, T, N, K, g, q, qt, 1.f, pf, w, wb, nullptr);
+                break;
+        }
+    }
+    return s;
+}
+

@@ -623,7 +623,7 @@ static bcq_status batch_check(int op, const bcq_batch_layer* layers, int64_t cou
 
 template <int MODE>
 static hipError_t launch_pre(const BatchHeader& h, const unsigned char* dev, unsigned char* ws, hipStream_t st) {
-    hipLaunchKernelGGL((quant_act_batched_kernel<MODE>), dim3(h.pre_blocks, h.pre_sets), dim3(256), 0, st,
+    BCQ_LAUNCH((quant_act_batched_kernel<MODE>), dim3(h.pre_blocks, h.pre_sets), dim3(256), 0, st,
                        reinterpret_cast<const BatchLayerDev*>(dev + h.layers_off),
                        reinterpret_cast<const uint2*>(dev + h.pre_map_off), ws, (int64_t)h.T, h.halves);
     return hipGetLastError();
@@ -634,7 +634,7 @@ static hipError_t launch_main_cfg(const BatchHeader& h, const unsigned char* dev
     static LdsLimit limit;
     hipError_t e = limit.ensure((const void*)stream_tile_batched_kernel<MODE, QP, RT, TWO>, TILE_LDS);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((stream_tile_batched_kernel<MODE, QP, RT, TWO>), dim3(h.tile_blocks), dim3(64 * TILE_WAVES), TILE_LDS,
+    BCQ_LAUNCH((stream_tile_batched_kernel<MODE, QP, RT, TWO>), dim3(h.tile_blocks), dim3(64 * TILE_WAVES), TILE_LDS,
                        st, reinterpret_cast<const BatchLayerDev*>(dev + h.layers_off),
                        reinterpret_cast<const BatchPiece*>(dev + h.tile_map_off), ws, h.T, h.scale);
     return hipGetLastError();
@@ -784,6 +784,15 @@ bcq_status bcq_linear_batched(const void* table_host, const void* table_device, 
         default: return BCQ_ERR_DTYPE;
     }
     return e == hipSuccess ? BCQ_OK : BCQ_ERR_DEVICE;
+}
+
+bcq_status bcq_batch_prepare(const void* table_host, size_t table_bytes) {
+    // a dry run of bcq_linear_batched: stand-in pointers, no launch
+    void* const p = reinterpret_cast<void*>((uintptr_t)1 << 20);
+    bcq::tl_dry_run = true;
+    const bcq_status s = bcq_linear_batched(table_host, p, table_bytes, p, ~(size_t)0, nullptr);
+    bcq::tl_dry_run = false;
+    return s;
 }
 
 }  // extern "C"

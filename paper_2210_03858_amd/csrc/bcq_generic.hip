@@ -145,10 +145,10 @@ hipError_t launch_fwd_generic(const uint32_t* packed, const float* alpha, const 
                               int64_t N, int64_t K, int64_t g, int q, void* y, hipStream_t st) {
     dim3 grid((unsigned)((T + GEN_TT - 1) / GEN_TT), (unsigned)((N + 3) / 4));
     if (dtype == 0)
-        hipLaunchKernelGGL(fwd_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)x,
+        BCQ_LAUNCH(fwd_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)x,
                            (float*)y, T, N, K, g, q);
     else
-        hipLaunchKernelGGL(fwd_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha, (const bf16_t*)x,
+        BCQ_LAUNCH(fwd_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha, (const bf16_t*)x,
                            (bf16_t*)y, T, N, K, g, q);
     return hipGetLastError();
 }
@@ -159,10 +159,10 @@ hipError_t launch_bwd_alpha_generic(const uint32_t* packed, const void* x, const
     (void)q;
     dim3 grid((unsigned)((N + 3) / 4));
     if (dtype == 0)
-        hipLaunchKernelGGL(bwd_alpha_generic_kernel<float>, grid, dim3(256), 0, st, packed, (const float*)x,
+        BCQ_LAUNCH(bwd_alpha_generic_kernel<float>, grid, dim3(256), 0, st, packed, (const float*)x,
                            (const float*)dy, dalpha, T, N, K, g, q_train, grad_scale);
     else
-        hipLaunchKernelGGL(bwd_alpha_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, (const bf16_t*)x,
+        BCQ_LAUNCH(bwd_alpha_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, (const bf16_t*)x,
                            (const bf16_t*)dy, dalpha, T, N, K, g, q_train, grad_scale);
     return hipGetLastError();
 }
@@ -171,10 +171,10 @@ hipError_t launch_bwd_input_generic(const uint32_t* packed, const float* alpha, 
                                     int64_t T, int64_t N, int64_t K, int64_t g, int q, void* dx, hipStream_t st) {
     dim3 grid((unsigned)((T + GEN_TT - 1) / GEN_TT), (unsigned)((K + 255) / 256));
     if (dtype == 0)
-        hipLaunchKernelGGL(bwd_input_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)dy,
+        BCQ_LAUNCH(bwd_input_generic_kernel<float>, grid, dim3(256), 0, st, packed, alpha, (const float*)dy,
                            (float*)dx, T, N, K, g, q);
     else
-        hipLaunchKernelGGL(bwd_input_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha,
+        BCQ_LAUNCH(bwd_input_generic_kernel<bf16_t>, grid, dim3(256), 0, st, packed, alpha,
                            (const bf16_t*)dy, (bf16_t*)dx, T, N, K, g, q);
     return hipGetLastError();
 }

@@ -73,6 +73,15 @@ struct LdsLimit {
     }
 };
 
+// ---- dry runs ---------------------------------------------------------------------------------------------------
+// bcq_prepare / bcq_batch_prepare walk through an entry point's host code with this flag set: path selection and the
+// one-time host-side set-up (raising a kernel's dynamic-LDS limit) happen as in a real call, the launches are skipped.
+extern thread_local bool tl_dry_run;
+#define BCQ_LAUNCH(...)                                   \
+    do {                                                  \
+        if (!::bcq::tl_dry_run) hipLaunchKernelGGL(__VA_ARGS__); \
+    } while (0)
+
 // ---- host-side argument checks shared by the source files that hold C-ABI entry points ------------------
 namespace host {
 constexpr int64_t kMaxDim = (int64_t)1 << 17;     // N, K

@@ -485,7 +485,7 @@ static hipError_t launch_gemm_cfg(const bf16_t* A, int64_t lda, const u32x4* fra
     const int tiles_m = (int)((M + Cfg::BMT - 1) / Cfg::BMT), tiles_n = (int)((NC + Cfg::BNT - 1) / Cfg::BNT);
     TileMap tmap;
     const unsigned wgs = make_tile_map(tiles_m, tiles_n, 1, 32 * Cfg::OCC, (double)Cfg::BMT, (double)Cfg::BNT, &tmap);
-    hipLaunchKernelGGL((gemm_kernel<TM, TN>), dim3(wgs), dim3(256), Cfg::LDS_B, st, A, lda, frag, C, ldc, M, NC, R, R16,
+    BCQ_LAUNCH((gemm_kernel<TM, TN>), dim3(wgs), dim3(256), Cfg::LDS_B, st, A, lda, frag, C, ldc, M, NC, R, R16,
                        tmap);
     return hipGetLastError();
 }
@@ -513,7 +513,7 @@ hipError_t launch_fwd_mfma(const uint32_t* packed, const float* alpha, const voi
     const int64_t R16 = round_up(K, RPAD) / 16;
     const int64_t ct = (N + 31) / 32;
     dim3 grid((unsigned)ct, (unsigned)((R16 / 2 + 7) / 8));
-    hipLaunchKernelGGL(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16, (u32x4*)workspace);
+    BCQ_LAUNCH(expand_fwd_kernel, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16, (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_gemm((const bf16_t*)x, K, (const u32x4*)workspace, (bf16_t*)y, N, T, N, K, R16, st);
@@ -525,10 +525,10 @@ hipError_t launch_bwd_input_mfma(const uint32_t* packed, const uint32_t* packed_
     const int64_t R16 = round_up(N, RPAD) / 16;
     dim3 grid((unsigned)(K / 32), (unsigned)((R16 / 2 + 7) / 8));
     if (packed_t && N % 32 == 0)
-        hipLaunchKernelGGL(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, g, q, R16,
+        BCQ_LAUNCH(expand_bwd_kernel<true>, grid, dim3(256), 0, st, packed_t, alpha, N, K, g, q, R16,
                            (u32x4*)workspace);
     else
-        hipLaunchKernelGGL(expand_bwd_kernel<false>, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16,
+        BCQ_LAUNCH(expand_bwd_kernel<false>, grid, dim3(256), 0, st, packed, alpha, N, K, g, q, R16,
                            (u32x4*)workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -965,7 +965,7 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     const int64_t gcols = pl.xg ? K : N, lcols = pl.xg ? N : K;
     {
         dim3 grid((unsigned)((gcols + 127) / 128), (unsigned)((pl.T16 * 2 + 15) / 16));
-        hipLaunchKernelGGL(transpose_frag_kernel, grid, dim3(256), 0, st, gact, T, gcols, pl.T16, frag);
+        BCQ_LAUNCH(transpose_frag_kernel, grid, dim3(256), 0, st, gact, T, gcols, pl.T16, frag);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -978,7 +978,7 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
         static LdsLimit limit;                                                                                        \
         hipError_t ea = limit.ensure((const void*)dalpha_kernel<XGV, QTV, FV>, (size_t)lds);                           \
         if (ea != hipSuccess) return ea;                                                                              \
-        hipLaunchKernelGGL((dalpha_kernel<XGV, QTV, FV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16,  \
+        BCQ_LAUNCH((dalpha_kernel<XGV, QTV, FV>), grid, dim3(256), lds, st, lact, lcols, lcols, frag, pl.T16,  \
                            packed, part, T, N, K, q_train, tmap, pl.splits, pl.per_split);                            \
     }
 #define BCQ_DA_Q(XGV, FV)                                  \
@@ -1011,10 +1011,10 @@ hipError_t launch_bwd_alpha_mfma(const uint32_t* packed, const void* x, const vo
     AdamWArgs oa = {};
     if (opt) oa = *opt;
     if (pl.fine)
-        hipLaunchKernelGGL(dalpha_reduce_fine_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
+        BCQ_LAUNCH(dalpha_reduce_fine_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
                            pl.splits, (int64_t)pl.tiles_k * 8, (int)(g / 32), grad_scale, oa);
     else
-        hipLaunchKernelGGL(dalpha_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
+        BCQ_LAUNCH(dalpha_reduce_kernel, rgrid, dim3(256), 0, st, (const float*)part, dalpha, rows, G,
                            pl.splits, pl.tiles_k, (int)(g == K ? pl.tiles_k : g / DA_TILE), grad_scale, oa);
     return hipGetLastError();
 }

@@ -11,7 +11,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(const float* __restrict__ da
 }
 
 hipError_t launch_adamw(const float* dalpha, int64_t count, AdamWArgs args, hipStream_t st) {
-    hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, dalpha, count, args);
+    BCQ_LAUNCH(adamw_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, dalpha, count, args);
     return hipGetLastError();
 }
 

@@ -94,14 +94,14 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint32_t* __restri
 hipError_t launch_pack(const int8_t* planes, int64_t total_words, uint32_t* packed, hipStream_t st) {
     int64_t threads = 2 * total_words;
     unsigned blocks = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, st, planes, total_words, packed);
+    BCQ_LAUNCH(pack_kernel, dim3(blocks), dim3(256), 0, st, planes, total_words, packed);
     return hipGetLastError();
 }
 
 hipError_t launch_unpack(const uint32_t* packed, int64_t total_words, int8_t* planes, hipStream_t st) {
     int64_t threads = 2 * total_words;
     unsigned blocks = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(unpack_kernel, dim3(blocks), dim3(256), 0, st, packed, total_words, planes);
+    BCQ_LAUNCH(unpack_kernel, dim3(blocks), dim3(256), 0, st, packed, total_words, planes);
     return hipGetLastError();
 }
 
@@ -109,7 +109,7 @@ hipError_t launch_pack_transposed(const uint32_t* packed, int64_t N, int64_t K, 
                                   hipStream_t st) {
     const int64_t Kw = K / 32, Nw = N / 32;
     dim3 grid((unsigned)((Kw + TR_WB - 1) / TR_WB), (unsigned)((Nw + TR_VB - 1) / TR_VB), (unsigned)q);
-    hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, st, packed, N, K, packed_t);
+    BCQ_LAUNCH(transpose_kernel, grid, dim3(256), 0, st, packed, N, K, packed_t);
     return hipGetLastError();
 }
 

@@ -177,10 +177,10 @@ static hipError_t launch_q(const float* W, int64_t N, int64_t K, int q, float* a
                            int8_t* planes, int* status_word, hipStream_t st) {
     const unsigned blocks = (unsigned)(WAVE_ROW ? (N + 3) / 4 : N);
     if (K == (int64_t)64 * (WAVE_ROW ? 1 : 4) * CMAX)
-        hipLaunchKernelGGL((quantize_kernel<CMAX, WAVE_ROW, true>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
+        BCQ_LAUNCH((quantize_kernel<CMAX, WAVE_ROW, true>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
                            alpha, packed, planes, status_word);
     else
-        hipLaunchKernelGGL((quantize_kernel<CMAX, WAVE_ROW, false>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
+        BCQ_LAUNCH((quantize_kernel<CMAX, WAVE_ROW, false>), dim3(blocks), dim3(256), 0, st, W, N, (int)K, q,
                            alpha, packed, planes, status_word);
     return hipGetLastError();
 }
@@ -188,7 +188,7 @@ static hipError_t launch_q(const float* W, int64_t N, int64_t K, int q, float* a
 hipError_t launch_quantize(const float* W, int64_t N, int64_t K, int q, float* alpha, uint32_t* packed,
                            int8_t* planes, int* status_word, hipStream_t st) {
     if (status_word) {
-        hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, st, status_word);
+        BCQ_LAUNCH(zero_word_kernel, dim3(1), dim3(1), 0, st, status_word);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -319,7 +319,7 @@ static hipError_t launch_small(const uint32_t* planes, const bf16_t* act, const 
         static LdsLimit limit;                                                                                     \
         const hipError_t le = limit.ensure((const void*)small_kernel<MODE, RR, QQ>, lds);                          \
         if (le != hipSuccess) return le;                                                                           \
-        hipLaunchKernelGGL((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
+        BCQ_LAUNCH((small_kernel<MODE, RR, QQ>), grid, block, lds, st, planes, act, alpha, dy, out, T, rows, cw, q, \
                            q_used, scale, p.segs_per_wave);                                                        \
     }
 #define BCQ_SMALL_Q(RR)                                          \

@@ -90,7 +90,7 @@ static hipError_t launch_lds_cfg(const uint32_t* planes, const unsigned char* xq
     static LdsLimit limit;
     hipError_t e = limit.ensure((const void*)stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>, LDS_B);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
+    BCQ_LAUNCH((stream_lds_kernel<MODE, QP, TWO, GROUPED, KW, EXACT, TILED>), dim3(lp.grid_x, (unsigned)tiles), dim3(512),
                        LDS_B, st, planes, xq, sq, alpha, dy, out, T, rows, cw, q_used, scale, lp.spp, segs, gsegs, G, xq_plane,
                        sq_plane, seg_magic, segs_n);
     return hipGetLastError();
@@ -176,7 +176,7 @@ static hipError_t launch_fused_cfg(const uint32_t* planes, const bf16_t* act, co
     static LdsLimit limit;
     hipError_t e = limit.ensure((const void*)stream_fused_kernel<MODE, QP, TWO>, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((stream_fused_kernel<MODE, QP, TWO>), dim3(p.grid_x, (unsigned)p.tiles), dim3((unsigned)(64 * p.W)),
+    BCQ_LAUNCH((stream_fused_kernel<MODE, QP, TWO>), dim3(p.grid_x, (unsigned)p.tiles), dim3((unsigned)(64 * p.W)),
                        lds, st, planes, act, alpha, dy, out, T, rows, cw, q_used, scale, p.segs_per_wave, p.segs, gsegs, G);
     return hipGetLastError();
 }
@@ -219,7 +219,7 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     {
         const int64_t threads = (int64_t)p.tiles * p.segs * 256;
         const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)sets);
-        hipLaunchKernelGGL((quant_act_kernel<MODE>), grid, dim3(256), 0, st, act, alpha, T, cw * 32, p.segs, p.halves,
+        BCQ_LAUNCH((quant_act_kernel<MODE>), grid, dim3(256), 0, st, act, alpha, T, cw * 32, p.segs, p.halves,
                            p.tiles, xq, sq, p.xq_bytes, p.sq_bytes, G);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -254,7 +254,7 @@ static hipError_t launch_stream(const uint32_t* planes, const bf16_t* act, const
     const int qp = q_used <= 4 ? q_used : 8;
     const bool quad = TILED || (cw % 4 == 0);  // the decode layout has one instantiation (the flag is unused there)
 #define BCQ_STREAM_GO(QQ, TT, QD, GR)                                                                                  \
-    hipLaunchKernelGGL((stream_kernel<MODE, 1, QQ, TT, QD, GR, TILED>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, \
+    BCQ_LAUNCH((stream_kernel<MODE, 1, QQ, TT, QD, GR, TILED>), grid, block, lds, st, planes, xq, sq, alpha, dy, out, T, \
                        rows, cw, q_used, scale, p.segs_per_wave, p.segs, p.xq_bytes, p.sq_bytes, 127,                  \
                        gsegs > 0 ? gsegs : 1, G, g)
 #define BCQ_STREAM_GR(QQ, TT, QD)            \
@@ -335,7 +335,7 @@ size_t decode_layout_bytes(int64_t N, int64_t K, int q) {
 hipError_t launch_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, uint32_t* tiled, hipStream_t st) {
     const int64_t segs = (K + 511) / 512;
     const int64_t units = (int64_t)(decode_layout_bytes(N, K, q) / 16);
-    hipLaunchKernelGGL(pack_decode_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, packed, N, K / 32, q, segs,
+    BCQ_LAUNCH(pack_decode_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, packed, N, K / 32, q, segs,
                        units, reinterpret_cast<q_u32x4*>(tiled));
     return hipGetLastError();
 }

@@ -199,6 +199,20 @@ def test_batch_plan_errors_and_layout_before_device(lib):
         assert lib.bcq_linear_batched(buf, A, tb.value, A, 1 << 30, None) == 7
 
 
+def test_prepare_errors_before_device(lib):
+    i64 = ctypes.c_int64
+    assert lib.bcq_prepare(9, 8, 64, 64, i64(64), 3, 1) == 3
+    assert lib.bcq_prepare(1, 8, 64, 48, i64(48), 3, 1) == 2
+    assert lib.bcq_prepare(1, 8, 64, 64, i64(48), 3, 1) == 2      # group size must divide K
+    assert lib.bcq_prepare(1, 8, 64, 64, i64(64), 3, 5) == 3
+    assert lib.bcq_batch_prepare(None, 1024) == 1
+    junk = ctypes.create_string_buffer(1024)
+    assert lib.bcq_batch_prepare(junk, 1024) == 3                  # not a plan
+    import torch
+    if not torch.cuda.is_available():
+        assert lib.bcq_prepare(1, 8, 64, 64, i64(64), 3, 1) == 7
+
+
 def test_no_device_is_reported(lib):
     import torch
     if torch.cuda.is_available():

@@ -75,12 +75,33 @@ def test_the_checker_sees_a_planted_early_use():
     assert len(_check(vmem_wait_only)[1]) == 1
 
 
-@pytest.mark.parametrize("tile", ["4ELi4", "2ELi2", "1ELi2", "1ELi1"])
-def test_no_instruction_touches_a_pending_fragment_read(mfma_asm, tile):
-    m = re.search(r"^_ZN3bcq11gemm_kernelILi%s\w*:[^\n]*\n(.*?)s_endpgm" % tile, mfma_asm, re.S | re.M)
-    assert m, "gemm_kernel<%s> not found in the assembly" % tile
-    lines = [l.strip() for l in m.group(1).split("\n")]
-    lines = [l for l in lines if l and not l.startswith(";") and not l.startswith(".")]
-    reads, violations = _check(lines)
-    assert reads >= 4, "the main loop's fragment reads were not found"
-    assert not violations, violations[:5]
+def _dispatcher_tiles():
+    """(TM, TN) of every gemm_kernel instantiation the host dispatcher can launch: read from its source."""
+    src = open(os.path.join(ROOT, "paper_2210_03858_amd", "csrc", "bcq_mfma.hip")).read()
+    body = src[src.index("static hipError_t launch_gemm("):]
+    body = body[:body.index("\n}\n")]
+    tiles = sorted(set((int(a), int(b)) for a, b in re.findall(r"launch_gemm_cfg<\s*(\d+)\s*,\s*(\d+)\s*>", body)))
+    assert len(tiles) >= 2, "the dispatcher's tile choices were not found"
+    return tiles
+
+
+def _kernel_bodies(asm):
+    """{(TM, TN): instruction lines} of every gemm_kernel instantiation in the assembly."""
+    out = {}
+    for m in re.finditer(r"^_ZN3bcq11gemm_kernelILi(\d+)ELi(\d+)E\w*:[^\n]*\n(.*?)s_endpgm", asm, re.S | re.M):
+        lines = [l.strip() for l in m.group(3).split("\n")]
+        out[(int(m.group(1)), int(m.group(2)))] = [l for l in lines if l and not l.startswith(";") and not l.startswith(".")]
+    return out
+
+
+def test_every_instantiation_the_dispatcher_can_launch_is_compiled_and_clean(mfma_asm):
+    """No hand-typed list: the tile configurations come from launch_gemm's source, and every gemm_kernel found in the
+    assembly is checked, so a new instantiation cannot slip past the guard."""
+    bodies = _kernel_bodies(mfma_asm)
+    for tile in _dispatcher_tiles():
+        assert tile in bodies, "gemm_kernel<%d, %d> is launched by the dispatcher but not in the assembly" % tile
+    assert set(bodies) == set(_dispatcher_tiles()), "instantiations in the assembly that the dispatcher never launches"
+    for tile, lines in bodies.items():
+        reads, violations = _check(lines)
+        assert reads >= 4, ("the main loop's fragment reads were not found", tile)
+        assert not violations, (tile, violations[:5])
