@@ -151,7 +151,16 @@ __device__ __forceinline__ void quant_act_body(const bf16_t* __restrict__ act, c
                                                size_t xq_plane, size_t sq_plane, int NG, int seg_mul, uint32_t bx,
                                                uint32_t by) {
     const int64_t idx = (int64_t)bx * 256 + threadIdx.x;
-    const int G = (int)(idx & 3), tl = (int)((idx >> 2) & 15), j = (int)((idx >> 6) & 3);
+    const bool one_half_map = (halves == 1);
+    // two halves: 4 blocks x 16 tokens x 4 instructions = 256 units per (tile, segment).  One half: only tokens 0 .. 7
+    // have units; they are mapped onto the first 128 threads so that two waves work with all lanes instead of four
+    // waves with half of them.
+    if (one_half_map && (threadIdx.x & 255) >= 128) return;
+    // the token index runs fastest over the lanes: the 16-byte stores of neighbouring lanes are then neighbours in the
+    // operand block (column = token), 128 or 256 bytes in a row instead of one piece per lane
+    const int tl = one_half_map ? (int)(idx & 7) : (int)(idx & 15);
+    const int G = one_half_map ? (int)((idx >> 3) & 3) : (int)((idx >> 4) & 3);
+    const int j = one_half_map ? (int)((idx >> 5) & 3) : (int)((idx >> 6) & 3);
     const int64_t seg = (idx >> 8) % segs, tile = (idx >> 8) / segs;
     if (tile >= tiles) return;
     const int plane = (int)by;
@@ -168,8 +177,18 @@ __device__ __forceinline__ void quant_act_body(const bf16_t* __restrict__ act, c
         if (MODE == STREAM_DX) {
             const int pl_i = plane / NG, grp = plane % NG;
             const float* a = alpha + ((int64_t)pl_i * C + word * 32) * NG + grp;  // alpha[i][n][grp], n = 32 word + e
+            if (NG == 1) {  // row-wise scales: 32 consecutive floats, 128-byte aligned (C is a multiple of 32)
+                const q_f32x4* a4 = reinterpret_cast<const q_f32x4*>(a);
 #pragma unroll
-            for (int e = 0; e < 32; ++e) v[e] *= a[(int64_t)e * NG];
+                for (int b = 0; b < 8; ++b) {
+                    const q_f32x4 av = a4[b];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[4 * b + e] *= av[e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 32; ++e) v[e] *= a[(int64_t)e * NG];
+            }
         }
     } else {
 #pragma unroll
