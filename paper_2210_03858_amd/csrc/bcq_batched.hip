@@ -100,9 +100,11 @@ __global__ __launch_bounds__(256) void quant_act_batched_kernel(const BatchLayer
 //     segments of the transposed twin (virtual segment v = segment * q + plane, each with its own activation set
 //     dy * alpha_plane; in the decode layout of the twin these ARE consecutive KiB), i.e. QP = 1, RT = 4.
 //   * A wave's work inside a chunk is a flat sequence of UNITS (group k, segment s).  The plane words of a unit are
-//     requested 4 units ahead into a ring of 4 register sets addressed by the unrolled position.  Every ring step
+//     requested TILE_RING units ahead into a ring of register sets addressed by the unrolled position (two units =
+//     8 KiB per wave: in address order the memory system needs no more; 4 and 8 measured equal or slower and cost
+//     registers).  Every ring step
 //     issues exactly one unit's requests, also where there is nothing left to multiply (the sequence is padded to a
-//     multiple of 4; the padding steps request the first units of the next chunk), so the number of requests between
+//     multiple of the ring length; the padding steps request the first units of the next chunk), so the number of requests between
 //     a request and its use is a compile-time constant and the compiler's wait counts are exact: a step waits for
 //     its own unit only, never for the younger requests behind it.
 //   * For the same reason nothing in the loop reads global memory but the planes: the epilogue operands of the whole
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(256) void quant_act_batched_kernel(const BatchLayer
 //   * Sign expansion with ONE operation per operand register: (word << s) | 0x77777777 turns bit b into the FP4 code
 //     0x7 | b << 3 = -6 (b = 1, i.e. +1) or +6 (b = 0, i.e. -1); the common factor -1/6 is applied in the epilogue.
 constexpr int TILE_WAVES = 4;
-constexpr int TILE_RING = 4;   // units in flight per wave
+constexpr int TILE_RING = 2;   // units in flight per wave
 constexpr int TILE_XB = 8 * 4 * QBLK, TILE_SB = 8 * QSCL;  // one chunk: 8 operand-block sets of 8 KiB + their scales
 constexpr int TILE_AUX = 12288;  // epilogue operands of the piece + sums carried between chunks
 constexpr int TILE_LDS = TILE_XB + TILE_SB + TILE_AUX;
