@@ -73,6 +73,9 @@ def parse():
     ap.add_argument("--replicas", type=int, default=0,
                     help="small-token stacks: independent copies of the block (own weights); default: enough for 512 MB "
                          "of packed planes, beyond the 256 MB Infinity Cache")
+    ap.add_argument("--setup-ops", type=int, default=-1,
+                    help="workload whose two MLP shapes the set-up kernels (quantize, pack, unpack, transposed twin, "
+                         "decode layout) are timed on, each alone; default: workload 5 in the default run, else none")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a kernel of known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -210,13 +213,6 @@ def run_large(args, env, config, T, q, steps, warmup, custom=None, context=True,
                 else:
                     run_op(L, op)
 
-    if args.calibrate_copy and headline:
-        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     # warm-up: every call bracketed by events -> per-op table and the roofline of the dominant op family
     warm_events = []
     n_warm = max(warmup, 2)  # at least two: the per-op figures skip the first step (one-time set-up of the kernels)
@@ -339,6 +335,54 @@ def run_large(args, env, config, T, q, steps, warmup, custom=None, context=True,
                   "algorithmic": "quantize: 4NK read + qNK/8 + 4qN written; twin: qNK/8 read + written"},
     }
     return res, layers
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# set-up operations (quantizer, Appendix C Eq. ap1-ap3; layouts of the planes): each kernel alone, on the two MLP shapes
+
+def run_setup_ops(env, config, q, iters=10):
+    np, torch, bcq, synth = env
+    cfg = synth.CONFIGS[config]
+    out = {}
+    gen = torch.Generator(device="cuda")
+    for kind in ("mlp_up", "mlp_down"):
+        N, K = synth.layer_shape(cfg["h"], kind)
+        gen.manual_seed(synth.seed_for(config, kind, 0))
+        W = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        alpha, packed, planes = bcq.bcq_quantize(W, q, want_planes=True)
+        twin = bcq.bcq_pack_transposed(packed)
+        tiled = bcq.bcq_pack_decode(packed)
+        a2, p2 = torch.empty_like(alpha), torch.empty_like(packed)
+        pb = q * N * K // 8
+        ops = {
+            # W read once; planes and scales written
+            "quantize": (lambda: bcq.bcq_quantize(W, q, alpha=a2, packed=p2), 4 * N * K + pb + 4 * q * N),
+            # one int8 per sign read, one bit written
+            "pack": (lambda: bcq.bcq_pack(planes, packed=p2), q * N * K + pb),
+            "unpack": (lambda: bcq.bcq_unpack(packed, planes_i8=planes), q * N * K + pb),
+            "pack_transposed": (lambda: bcq.bcq_pack_transposed(packed, packed_t=twin), 2 * pb),
+            "pack_decode": (lambda: bcq.bcq_pack_decode(packed, tiled=tiled), pb + tiled.numel() * tiled.element_size()),
+        }
+        r = {}
+        for name, (fn, nbytes) in ops.items():
+            fn()
+            torch.cuda.synchronize()
+            # one captured graph of `iters` calls: a call from Python costs more than these 10-30 us kernels run
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(iters):
+                    fn()
+            graph.replay()
+            ms = timed_events(torch, graph.replay, 3) / iters
+            del graph
+            r[name] = {"us": round(ms * 1e3, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                       "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        out["%s_%dx%d_q%d" % (kind, N, K, q)] = r
+        del W, alpha, packed, planes, twin, tiled, a2, p2
+        torch.cuda.empty_cache()
+    out["algorithmic"] = ("quantize 4NK + qNK/8 + 4qN; pack/unpack qNK + qNK/8; transposed twin 2*qNK/8; decode layout "
+                          "qNK/8 read + the padded tiled size written; events around 3 replays of a HIP graph of %d calls" % iters)
+    return out
 
 
 # ------------------------------------------------------------------------------------------------------------------
@@ -522,6 +566,13 @@ def main():
         custom = tuple(int(v) for v in args.layer.lower().split("x"))
         assert len(custom) == 2 and custom[1] % 32 == 0, "--layer wants NxK with K % 32 == 0"
 
+    if args.calibrate_copy:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     small = T <= 16 and cfg["dtype"] == "bf16" and not args.g
     cpu = None
     if small:
@@ -551,6 +602,11 @@ def main():
         torch.cuda.empty_cache()
         regimes[name] = r
 
+    setup_ops = None
+    so = args.setup_ops if args.setup_ops >= 0 else (5 if wanted and args.regimes == "all" else 0)
+    if so:
+        setup_ops = run_setup_ops(env, so, synth.CONFIGS[so]["q"][-1])
+
     out = {
         "metric": metric,
         "value": value,
@@ -571,6 +627,7 @@ def main():
         "context": head.get("context"),
         "per_op": head["per_op"],
         "setup": head["setup"],
+        "setup_ops": setup_ops,
         "regimes": regimes,
         "targets": {"large_token": ">= 0.50 of the bf16 MFMA peak at >= 2048 tokens", "small_token": ">= 0.70 of the HBM peak "
                     "at <= 8 tokens", "status": "both open: see roofline.frac of the headline and of the regimes"},

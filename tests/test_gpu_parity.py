@@ -93,6 +93,36 @@ def test_quantize_bit_exact(bcq, oracle, q, N, K):
     _check_quantize(bcq, oracle, W, q)
 
 
+@pytest.mark.parametrize("K", [256, 512, 768, 1024, 1280, 1536, 2048, 2560, 3072, 4096, 5120, 6144, 8192, 10240])
+def test_quantize_rows_of_256_column_chunks(bcq, oracle, K):
+    # every chunk count of the form for rows of whole 256-column chunks (1, 2 or 4 waves per row), ragged N
+    W = synth.weights(1, "out", 37, K, extra=K + 1)
+    _check_quantize(bcq, oracle, W, 3)
+
+
+@pytest.mark.parametrize("q,N,K", [(2, 6151, 512), (1, 3301, 5120), (3, 1001, 8192), (4, 3075, 2560)])
+def test_quantize_more_rows_than_one_round_of_workgroups(bcq, oracle, q, N, K):
+    W = synth.weights(1, "out", N, K, extra=N)
+    _check_quantize(bcq, oracle, W, q, want_planes=False)
+
+
+def test_quantize_residuals_that_hit_zero_exactly(bcq, oracle):
+    # |w| constant along a row: the first mean equals every magnitude, all residuals become +0.0 and every later
+    # plane is all +1; two magnitudes c and 3 c: zero after the second plane (Appendix C, Eq. ap1 - ap3)
+    rng = np.random.default_rng(5)
+    W = np.empty((24, 1024), dtype=np.float32)
+    for n in range(24):
+        sign = rng.choice(np.float32([-1.0, 1.0]), size=1024)
+        c = np.float32(2.0 ** (n % 5 - 3) * 1.25)
+        mag = np.full(1024, c, dtype=np.float32)
+        if n % 2:
+            mag[rng.permutation(1024)[:512]] = np.float32(3.0) * c
+        W[n] = sign * mag
+    a_ref, b_ref = oracle.quantize(W, 4)
+    assert (b_ref[2:] == 1).all()  # the case is the one meant
+    _check_quantize(bcq, oracle, W, 4)
+
+
 def test_quantize_outliers_zero_rows_no_planes(bcq, oracle):
     W = synth.weights(4, "qkv", 2048, 2048, outliers=True)
     W[5] = 0.0
