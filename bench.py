@@ -291,7 +291,8 @@ def run_large(args, env, config, T, q, steps, warmup, custom=None, context=True,
                     "algorithmic": "2*T*N*K flops per call, averaged over the %d layer shapes; the family's helper "
                                    "kernels are inside the event time" % len(layers),
                     "note": "HIP events around each call of the slowest operation family in the %d eagerly launched "
-                            "one-stream warm-up steps of this run; per-kernel durations: profiles/" % (n_warm - 1)}
+                            "one-stream warm-up steps of this run; per-kernel durations and matrix-core counters: "
+                            "profiles/large_token_kernel_stats.md, profiles/large_token_mfma_counters.md" % (n_warm - 1)}
 
     ctx = None
     if context and not args.no_context and dtype == "bf16":
@@ -469,7 +470,8 @@ def run_stack(args, env, config, T, q, custom=None, iters=20):
                 "avg_launch_us": round(op_ms[dom] * 1e3, 2), "launches_per_step": 1,
                 "algorithmic": "per call over the stack: q*N*K/8 plane bytes + 4*q*N + 2*T*(K+N) per layer",
                 "note": "HIP events around %d back-to-back batched calls of the slowest operation (pre-kernel + main "
-                        "kernel); the planes are read once by each of fwd, dx, dalpha" % iters}
+                        "kernel); the planes are read once by each of fwd, dx, dalpha; per-kernel durations: "
+                        "profiles/small_token_stack_kernel_stats.md" % iters}
     flops_step = 6.0 * T * sum(L["N"] * L["K"] for L in layers)
     res = {
         "workload": "config %d: stack of %d x (%s) layers of width %d (%d layers, %.1f MB of packed planes), q=%d, row-wise "
