@@ -16,8 +16,9 @@ The default run prints ONE JSON line:
   * `cpu_baseline`: the CPU oracle timed on a bounded sample of the headline workload.
 A single regime can be run alone with --config / --tokens / --q (and --regimes none).
 
-Roofline figures: `achieved` is the algorithmic work of an operation family (one C-ABI call, all its kernels) divided
-by its HIP-event time; for the large-token regimes the events bracket the calls in the eagerly launched one-stream
+Roofline figures: `achieved` is the algorithmic work of a kernel family (gemm_kernel = forward + input gradient calls,
+dalpha_kernel = scale gradient calls; the one with the largest share of the step, the slowest operation beside it; each
+C-ABI call with all its kernels) divided by its HIP-event time; for the large-token regimes the events bracket the calls in the eagerly launched one-stream
 warm-up steps of the same run (the timed region replays a HIP graph over two streams, inside which no event can be
 recorded); for the small-token stacks they bracket the batched calls themselves.  `traffic` is not measured live: it
 is read from the table in profiles/hbm_traffic.md (rocprofv3 --pmc runs of this file's commands) and labelled so.
@@ -272,27 +273,45 @@ def run_large(args, env, config, T, q, steps, warmup, custom=None, context=True,
         per_op = {op: {"ms_per_step": round(fam_ms[op], 4), "tflops": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12, 3),
                        "frac_of_peak": round(fam_flops / (fam_ms[op] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4)}
                   for op in ops}
-        dom = max(fam_ms, key=lambda k: fam_ms[k])
-        main_kernel = {"fwd": "gemm_kernel (+ expand_fwd_kernel)", "bwd_input": "gemm_kernel (+ expand_bwd_kernel)",
-                       "bwd_alpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}[dom]
+        # Kernel families of a step: gemm_kernel serves the forward and the input gradient (two calls per layer, each with
+        # its short expand kernel), dalpha_kernel the scale gradient (one call per layer, with its transpose and reduce
+        # kernels).  `roofline` is the family with the largest share of the step's time; the slowest single operation
+        # family is reported beside it.
+        kern = {"gemm": ("fwd", "bwd_input"), "dalpha": ("bwd_alpha",)}
+        kern_ms = {k: sum(fam_ms[o] for o in v) for k, v in kern.items()}
+        domk = max(kern_ms, key=lambda k: kern_ms[k])
+        slow = max(fam_ms, key=lambda k: fam_ms[k])
+        names = {"gemm": "gemm_kernel (+ expand_fwd_kernel / expand_bwd_kernel)",
+                 "dalpha": "dalpha_kernel (+ transpose_frag_kernel, dalpha_reduce_kernel)"}
         bound, peak = "mfma", PEAK_BF16_MFMA_TFLOPS
         if dtype != "bf16":
             # fp32 activations take the any-shape vector-ALU kernels, which execute q plane products (2 q T N K lane
             # operations for 2 T N K effective flops): priced against the fp32 vector peak of the chip
-            bound, peak, main_kernel = "alu", PEAK_FP32_VECTOR_TFLOPS, "%s_generic_kernel" % dom
-        achieved = fam_flops / (fam_ms[dom] * 1e-3) / 1e12
-        tkey = "config%d_T%d_q%d_%s" % (config, T, q, dom)
-        traffic = traffic_from_profile(tkey) if not (args.g or custom) else None
-        roofline = {"bound": bound, "kernel": main_kernel, "op": "bcq_linear_" + dom, "achieved": round(achieved, 3),
-                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 5), "traffic": traffic,
-                    "traffic_source": ("profiles/hbm_traffic.md row %s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-scaled; "
-                                       "not measured in this run)" % tkey) if traffic else None,
-                    "avg_launch_us": round(fam_ms[dom] * 1e3 / len(layers), 2), "launches_per_step": len(layers),
+            bound, peak = "alu", PEAK_FP32_VECTOR_TFLOPS
+            names = {"gemm": "fwd_generic_kernel, bwd_input_generic_kernel", "dalpha": "bwd_alpha_generic_kernel"}
+        calls = len(kern[domk]) * len(layers)
+        achieved = len(kern[domk]) * fam_flops / (kern_ms[domk] * 1e-3) / 1e12
+        traffic, tkeys = None, ["config%d_T%d_q%d_%s" % (config, T, q, o) for o in kern[domk]]
+        if not (args.g or custom):
+            rows = [traffic_from_profile(k) for k in tkeys]
+            traffic = sum(rows) / len(rows) if all(r is not None for r in rows) else None
+        slow_achieved = fam_flops / (fam_ms[slow] * 1e-3) / 1e12
+        roofline = {"bound": bound, "kernel": names[domk], "op": " + ".join("bcq_linear_" + o for o in kern[domk]),
+                    "time_share": round(kern_ms[domk] / sum(kern_ms.values()), 4),
+                    "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 5),
+                    "traffic": traffic,
+                    "traffic_source": ("profiles/hbm_traffic.md rows %s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE per call, "
+                                       "copy-scaled; not measured in this run)" % ", ".join(tkeys)) if traffic else None,
+                    "avg_launch_us": round(kern_ms[domk] * 1e3 / calls, 2), "launches_per_step": calls,
                     "algorithmic": "2*T*N*K flops per call, averaged over the %d layer shapes; the family's helper "
                                    "kernels are inside the event time" % len(layers),
-                    "note": "HIP events around each call of the slowest operation family in the %d eagerly launched "
-                            "one-stream warm-up steps of this run; per-kernel durations and matrix-core counters: "
-                            "profiles/large_token_kernel_stats.md, profiles/large_token_mfma_counters.md" % (n_warm - 1)}
+                    "slowest_family": {"op": "bcq_linear_" + slow, "achieved": round(slow_achieved, 3),
+                                       "frac": round(slow_achieved / peak, 5),
+                                       "avg_launch_us": round(fam_ms[slow] * 1e3 / len(layers), 2)},
+                    "note": "HIP events around each call in the %d eagerly launched one-stream warm-up steps of this run "
+                            "(the family with the largest time share; the slowest operation family beside it); per-kernel "
+                            "durations and matrix-core counters: profiles/large_token_kernel_stats.md, "
+                            "profiles/large_token_mfma_counters.md" % (n_warm - 1)}
 
     ctx = None
     if context and not args.no_context and dtype == "bf16":
