@@ -441,6 +441,8 @@ def run_stack(args, env, config, T, q, custom=None, iters=20):
                      dalpha=torch.empty((q, N), dtype=torch.float32, device="cuda"))
             if args.layer_by_layer:
                 L["packed"], L["twin"] = packed, twin
+            elif T == 1:  # the table look-up variant of the forward is timed beside the batched one
+                L["packed"] = packed
             layers.append(L)
             del packed, twin
     e1.record()
@@ -506,6 +508,23 @@ def run_stack(args, env, config, T, q, custom=None, iters=20):
         "setup": {"stack_ms": round(setup_ms, 2), "note": "random weights, greedy quantizer, twin and two decode layouts "
                                                            "per layer, launched from Python"},
     }
+    if T == 1 and all("packed" in L and 8 * L["K"] <= 128 * 1024 for L in layers):
+        # Section 6 "Inference Speed": forward by table look-up, one call per layer, the stack captured in one HIP graph
+        def lut():
+            for L in layers:
+                bcq.bcq_linear_fwd_lut(L["packed"], L["alpha"], L["x"], y=L["y"])
+        lut()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lut()
+        graph.replay()
+        ms = timed_events(torch, graph.replay, 5)
+        del graph
+        res["lut_forward"] = {"ms": round(ms, 4), "packed_weight_GBps": round(planes / (ms * 1e-3) / 1e9, 1),
+                              "frac_of_hbm_peak": round((planes + other["fwd"]) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                              "note": "bcq_linear_fwd_lut per layer (lut_fwd_kernel), %d calls in one HIP graph; compare "
+                                      "per_op.fwd (one batched call on the FP4 x FP8 matrix instruction)" % len(layers)}
     if args.layer_by_layer:
         ws = {}
         for L in layers:

@@ -92,7 +92,7 @@ const char* bcq_status_string(bcq_status s);
 
 /* ABI version, bumped on any signature change or addition (2: *_grouped entry points; 3: bcq_quantize_alternating; 4: AdamW entry points;
  * 5: decode layout; 6: bcq_linear_fwd_static;
- * 7: batched small-token calls; 8: bcq_prepare, bcq_batch_prepare). */
+ * 7: batched small-token calls; 8: bcq_prepare, bcq_batch_prepare; 9: bcq_linear_fwd_lut). */
 int bcq_abi_version(void);
 
 /* Scratch size (bytes) that enables the fastest path of `op` for this problem; *out may be 0.
@@ -175,6 +175,22 @@ bcq_status bcq_pack_decode(const uint32_t* packed, int64_t N, int64_t K, int q, 
 bcq_status bcq_linear_fwd_decode(const uint32_t* tiled, const float* alpha, const void* x, int dtype, int64_t T,
                                  int64_t N, int64_t K, int64_t g, int q, void* y, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/* Forward (Eq. 2) for decode by table look-up (Section 6, "Inference Speed": the route the paper names for fast
+ * small-batch inference), a selectable variant of bcq_linear_fwd for 1 .. BCQ_LUT_MAX_TOKENS tokens of bf16
+ * activations and row-wise scales.  Every group of 4 columns of x gives a table of its 16 signed sums (8 stored, the
+ * rest by sign), built in LDS by every workgroup; the nibbles of the canonical packed words index it; alpha is
+ * applied once per plane and row; fp32 accumulation, y rounded to bf16.  No workspace, nothing allocated.
+ *   packed [q][N][K/32] in; alpha [q][N] fp32 in; x [T][K] bf16 in; y [T][N] bf16 out.
+ * Errors: BCQ_ERR_DTYPE unless dtype == BCQ_BF16; BCQ_ERR_SHAPE for T > BCQ_LUT_MAX_TOKENS or tables larger than
+ * BCQ_LUT_MAX_TABLE_BYTES (8 * T * K bytes of LDS: T = 1 any K <= 16384, T = 4 K <= 4096) and the usual shape limits;
+ * BCQ_ERR_NULL, BCQ_ERR_ALIGN, BCQ_ERR_DEVICE as for bcq_linear_fwd.
+ * On gfx950 the default small-token path (FP4 x FP8 matrix instruction) is the faster one at every token count;
+ * this entry point exists so that the two can be compared. */
+#define BCQ_LUT_MAX_TOKENS 4
+#define BCQ_LUT_MAX_TABLE_BYTES (128 * 1024)
+bcq_status bcq_linear_fwd_lut(const uint32_t* packed, const float* alpha, const void* x, int dtype, int64_t T,
+                              int64_t N, int64_t K, int q, void* y, void* stream);
 
 /* Forward (Eq. 2): y[t][n] = sum_i alpha_i[n] * sum_k B_i[n][k] * x[t][k], fp32 accumulation,
  * result rounded to `dtype` (bf16: round to nearest even).  The dequantised W exists at most as a transient bf16

@@ -22,7 +22,7 @@ EXPORTS = ("bcq_status_string", "bcq_abi_version", "bcq_workspace_bytes", "bcq_q
            "bcq_workspace_bytes_grouped", "bcq_quantize_grouped", "bcq_linear_fwd_grouped",
            "bcq_linear_bwd_input_grouped", "bcq_linear_bwd_alpha_grouped", "bcq_quantize_alternating",
            "bcq_alpha_adamw_step", "bcq_linear_bwd_alpha_adamw", "bcq_decode_layout_bytes", "bcq_pack_decode",
-           "bcq_linear_fwd_decode", "bcq_linear_fwd_static", "bcq_batch_sizes", "bcq_batch_plan", "bcq_linear_batched",
+           "bcq_linear_fwd_decode", "bcq_linear_fwd_static", "bcq_linear_fwd_lut", "bcq_batch_sizes", "bcq_batch_plan", "bcq_linear_batched",
            "bcq_prepare", "bcq_batch_prepare")
 
 _lib = None
@@ -82,6 +82,7 @@ def load():
     lib.bcq_pack_decode.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.bcq_linear_fwd_decode.argtypes = [vp, vp, vp, i32, i64, i64, i64, i64, i32, vp, vp, sz, vp]
     lib.bcq_linear_fwd_static.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
+    lib.bcq_linear_fwd_lut.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, vp, vp]
     bl = ctypes.POINTER(BatchLayer)
     lib.bcq_batch_sizes.argtypes = [i32, bl, i64, i64, i32, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.bcq_batch_plan.argtypes = [i32, bl, i64, i64, i32, i32, f32, i32, vp, sz]
@@ -251,6 +252,26 @@ def bcq_linear_fwd(packed, alpha, x, y=None, workspace=None):
     wp, wb = _ws(workspace)
     _check(load().bcq_linear_fwd(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, q, _ptr(y), wp, wb, _stream()),
            "bcq_linear_fwd")
+    return y
+
+
+LUT_MAX_TOKENS = 4
+LUT_MAX_TABLE_BYTES = 128 * 1024
+
+
+def bcq_linear_fwd_lut(packed, alpha, x, y=None):
+    """Decode forward by table look-up (1 .. 4 tokens, bf16, row-wise scales, 8 * T * K <= 128 KiB); no workspace."""
+    q, N, Kw = packed.shape
+    K = Kw * 32
+    T = x.shape[0]
+    dt = _act_dtype(x)
+    _need(packed, torch.int32, (q, N, Kw), "packed")
+    _need(alpha, torch.float32, (q, N), "alpha")
+    _need(x, x.dtype, (T, K), "x")
+    y = torch.empty((T, N), dtype=x.dtype, device=x.device) if y is None else y
+    _need(y, x.dtype, (T, N), "y")
+    _check(load().bcq_linear_fwd_lut(_ptr(packed), _ptr(alpha), _ptr(x), dt, T, N, K, q, _ptr(y), _stream()),
+           "bcq_linear_fwd_lut")
     return y
 
 

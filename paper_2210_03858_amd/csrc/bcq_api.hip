@@ -135,7 +135,7 @@ const char* bcq_status_string(bcq_status s) {
     return "unknown status";
 }
 
-int bcq_abi_version(void) { return 8; }
+int bcq_abi_version(void) { return 9; }
 
 bcq_status bcq_workspace_bytes_grouped(int op, int64_t T, int64_t N, int64_t K, int64_t g, int q, int dtype,
                                        size_t* out) {
@@ -482,6 +482,9 @@ extern "C" bcq_status bcq_prepare(int op, int64_t T, int64_t N, int64_t K, int64
                 if (s == BCQ_OK && with_ws && g == K && dtype == BCQ_BF16 && T <= BCQ_STATIC_MAX_TOKENS &&
                     bcq::stream_fwd_workspace(T, K) <= (size_t)BCQ_STATIC_SCRATCH_BYTES)
                     s = bcq_linear_fwd_static(pu, pf, p, dtype, T, N, K, q, p, nullptr);
+                if (s == BCQ_OK && with_ws && g == K && dtype == BCQ_BF16 && T <= BCQ_LUT_MAX_TOKENS &&
+                    (size_t)T * (size_t)K * 8 <= (size_t)BCQ_LUT_MAX_TABLE_BYTES)
+                    s = bcq_linear_fwd_lut(pu, pf, p, dtype, T, N, K, q, p, nullptr);
                 break;
             case BCQ_OP_BWD_INPUT:
                 s = bcq_linear_bwd_input_grouped(pu, nullptr, pf, p, dtype, T, N, K, g, q, p, w, wb, nullptr);

@@ -130,6 +130,20 @@ def test_decode_layout_errors_before_device(lib):
     assert lib.bcq_linear_fwd_decode(A, A, A + 2, 1, T, N, K, i64(K), q, A, A, ws, None) == 4
 
 
+def test_fwd_lut_errors_before_device(lib):
+    q, N, K, T = 3, 64, 1024, 2
+    assert lib.bcq_linear_fwd_lut(A, A, A, 1, T, N, K, q, None, None) == 1
+    assert lib.bcq_linear_fwd_lut(A, A, A, 1, 5, N, K, q, A, None) == 2          # at most 4 tokens
+    assert lib.bcq_linear_fwd_lut(A, A, A, 1, 4, N, 4096 + 32, q, A, None) == 2  # tables beyond 128 KiB of LDS
+    assert lib.bcq_linear_fwd_lut(A, A, A, 1, 1, N, 16384 + 32, q, A, None) == 2
+    assert lib.bcq_linear_fwd_lut(A, A, A, 1, T, N, 1000, q, A, None) == 2
+    assert lib.bcq_linear_fwd_lut(A, A, A, 0, T, N, K, q, A, None) == 3          # bf16 only
+    assert lib.bcq_linear_fwd_lut(A, A, A + 4, 1, T, N, K, q, A, None) == 4
+    import torch
+    if not torch.cuda.is_available():
+        assert lib.bcq_linear_fwd_lut(A, A, A, 1, 1, N, 16384, q, A, None) == 7   # fits; no device here
+
+
 def test_fwd_static_errors_before_device(lib):
     q, N, K, T = 3, 64, 1024, 8
     assert lib.bcq_linear_fwd_static(A, A, A, 1, T, N, K, q, None, None) == 1
