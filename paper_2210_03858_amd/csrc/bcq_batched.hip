@@ -128,6 +128,21 @@ __host__ __device__ constexpr int tile_part_bytes(int rt, int nrtg, int halves) 
     return ((nrtg + TILE_WAVES - 1) / TILE_WAVES) * TILE_WAVES * rt * tile_part_slot(halves);
 }
 
+// Moves inside a row of 16 lanes with the data-parallel primitives of the vector ALU (a few cycles; a shuffle through
+// the LDS crossbar costs an LDS instruction and its latency).  All patterns used are permutations of the row.
+template <int CTRL>
+__device__ __forceinline__ float row16_move(float v) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a row, in every lane: neighbours, pairs, mirrored halves of 8, mirrored row
+__device__ __forceinline__ float row16_sum(float x) {
+    x += row16_move<0xB1>(x);   // quad_perm [1, 0, 3, 2]
+    x += row16_move<0x4E>(x);   // quad_perm [2, 3, 0, 1]
+    x += row16_move<0x141>(x);  // lane i of each 8 takes lane 7 - i
+    x += row16_move<0x140>(x);  // lane i takes lane 15 - i
+    return x;
+}
+
 template <int MODE, int QP, int RT, bool TWO>
 __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const BatchLayerDev* __restrict__ layers,
                                                                       const BatchPiece* __restrict__ pieces,
@@ -371,10 +386,7 @@ __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const Batch
                                         // one half: columns t and t + 8 both carry dy of token t; the 16-lane sum adds the
                                         // terms and the tokens
                                         float x = dyv[v] * acc[r][o][v];
-                                        x += __shfl_xor(x, 1);
-                                        x += __shfl_xor(x, 2);
-                                        x += __shfl_xor(x, 4);
-                                        x += __shfl_xor(x, 8);
+                                        x = row16_sum(x);
                                         sum[v] = x;
                                     }
                                     if (rl == 0) {
@@ -406,7 +418,7 @@ __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const Batch
                                 }
                                 if (!TWO) {  // second term's column onto the first's
 #pragma unroll
-                                    for (int v = 0; v < 4; ++v) val[v] += __shfl_xor(val[v], 8);
+                                    for (int v = 0; v < 4; ++v) val[v] += row16_move<0x128>(val[v]);  // from lane ^ 8
                                 }
                                 if (TWO || rl < 8) {
                                     q_f32x4* ps = reinterpret_cast<q_f32x4*>(slot + (TWO ? lane : g * 8 + rl) * 16);
