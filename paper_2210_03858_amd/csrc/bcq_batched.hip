@@ -89,20 +89,21 @@ __global__ __launch_bounds__(256) void quant_act_batched_kernel(const BatchLayer
 
 // ---------------------------------------------------------------------------------------------------------------------
 // The main kernel.  Written for many small layers rather than one large one:
-//   * A workgroup (4 waves) owns a PIECE: a run of row-tile groups of one layer.  It copies the layer's re-coded
-//     activations into LDS once per piece (in chunks of 66 KiB: 8 segments at up to 8 tokens, where both FP8 terms of a
-//     token sit in one instruction, 4 segments at 9 .. 16 tokens; most layers are one or two chunks), two
-//     workgroups fit a compute unit, and between the chunk copies the waves run free of each other: no barrier in
-//     the streaming loop, every wave walks its own row-tile groups (wave w takes group w, w + 4, ...).
+//   * A workgroup (8 waves, one per compute unit, 256 registers per lane) owns a PIECE: a run of row-tile groups of
+//     one layer.  It copies the layer's re-coded activations into LDS once per piece (in chunks of 132 KiB: 16 segments
+//     at up to 8 tokens, where both FP8 terms of a token sit in one instruction, 8 segments at 9 .. 16 tokens; most
+//     layers are one chunk), and between the chunk copies the waves run free of each other: no barrier in the
+//     streaming loop, every wave walks its own row-tile groups (wave w takes group w, w + 8, ...).  (Two workgroups
+//     of 4 waves with chunks of 8 segments were measured 1 - 8 % slower: every piece reads its layer's activation
+//     sets, the input gradient's q sets per segment above all, and twice the rows per piece halve that traffic.)
 //   * A wave multiplies PR = QP * RT "plane rows" per segment with one read of the activation operand from LDS:
 //     QP planes of RT row tiles (q = 1: four row tiles; q = 2: two; q = 3, 4: one), so the LDS traffic per plane byte
 //     does not grow when there are few planes.  The input gradient is one virtual plane over q * segs_act virtual
 //     segments of the transposed twin (virtual segment v = segment * q + plane, each with its own activation set
 //     dy * alpha_plane; in the decode layout of the twin these ARE consecutive KiB), i.e. QP = 1, RT = 4.
 //   * A wave's work inside a chunk is a flat sequence of UNITS (group k, segment s).  The plane words of a unit are
-//     requested TILE_RING units ahead into a ring of register sets addressed by the unrolled position (two units =
-//     8 KiB per wave: in address order the memory system needs no more; 4 and 8 measured equal or slower and cost
-//     registers).  Every ring step
+//     requested TILE_RING units ahead into a ring of register sets addressed by the unrolled position (three units =
+//     12 KiB per wave; two measured equal at up to 8 tokens and slower at 16, four slower at 8).  Every ring step
 //     issues exactly one unit's requests, also where there is nothing left to multiply (the sequence is padded to a
 //     multiple of the ring length; the padding steps request the first units of the next chunk), so the number of requests between
 //     a request and its use is a compile-time constant and the compiler's wait counts are exact: a step waits for
@@ -111,12 +112,23 @@ __global__ __launch_bounds__(256) void quant_act_batched_kernel(const BatchLayer
 //     piece (alpha, or dy for the scale gradient) and the sums carried from chunk to chunk sit in LDS.
 //   * Sign expansion with ONE operation per operand register: (word << s) | 0x77777777 turns bit b into the FP4 code
 //     0x7 | b << 3 = -6 (b = 1, i.e. +1) or +6 (b = 0, i.e. -1); the common factor -1/6 is applied in the epilogue.
-constexpr int TILE_WAVES = 4;
-constexpr int TILE_RING = 2;   // units in flight per wave
-constexpr int TILE_XB = 8 * 4 * QBLK, TILE_SB = 8 * QSCL;  // one chunk: 8 operand-block sets of 8 KiB + their scales
-constexpr int TILE_AUX = 12288;  // epilogue operands of the piece + sums carried between chunks
+#ifndef TILE_WAVES_N
+#define TILE_WAVES_N 8  // 4 is supported too (then two workgroups per compute unit, chunks of half the size)
+#endif
+constexpr int TILE_WAVES = TILE_WAVES_N;
+constexpr int TILE_THREADS = 64 * TILE_WAVES;
+#ifndef TILE_RING_N
+#define TILE_RING_N 3
+#endif
+constexpr int TILE_RING = TILE_RING_N;   // units in flight per wave
+#ifndef TILE_SETS_N
+#define TILE_SETS_N (2 * TILE_WAVES_N)
+#endif
+constexpr int TILE_SETS = TILE_SETS_N;  // operand-block sets of 8 KiB (+ 256 B of scales) in one chunk
+constexpr int TILE_XB = TILE_SETS * 4 * QBLK, TILE_SB = TILE_SETS * QSCL;
+constexpr int TILE_AUX = 3072 * TILE_WAVES;  // epilogue operands of the piece + sums carried between chunks
 constexpr int TILE_LDS = TILE_XB + TILE_SB + TILE_AUX;
-__host__ __device__ constexpr int tile_cseg(int halves) { return 8 / halves; }  // segments per chunk, at most
+__host__ __device__ constexpr int tile_cseg(int halves) { return TILE_SETS / halves; }  // segments per chunk, at most
 // carried sums of one row tile: the live lanes x 16 B (the scale gradient needs QP x 64 B, which is less)
 __host__ __device__ constexpr int tile_part_slot(int halves) { return halves == 2 ? 1024 : 512; }
 
@@ -144,7 +156,7 @@ __device__ __forceinline__ float row16_sum(float x) {
 }
 
 template <int MODE, int QP, int RT, bool TWO>
-__global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const BatchLayerDev* __restrict__ layers,
+__global__ __launch_bounds__(TILE_THREADS, 8 / TILE_WAVES) void stream_tile_batched_kernel(const BatchLayerDev* __restrict__ layers,
                                                                       const BatchPiece* __restrict__ pieces,
                                                                       const unsigned char* __restrict__ ws, int T,
                                                                       float scale) {
@@ -299,21 +311,23 @@ __global__ __launch_bounds__(256, 2) void stream_tile_batched_kernel(const Batch
         const int seg0 = c * cseg;
         const int nseg = chunk_nseg(c);
         // chunk copy: nseg x H operand-block sets of 8 KiB + nseg x H x 256 B of scales, global -> registers -> LDS; all
-        // (up to sixteen) 4 KiB units of 256 threads x 16 B are requested before the first is written
+        // (up to sixteen) steps of all threads x 16 B are requested before the first is written
         {
             const q_u32x4* src = reinterpret_cast<const q_u32x4*>(xq + (size_t)seg0 * (4 * H * QBLK)) + tid;
             q_u32x4* dst = reinterpret_cast<q_u32x4*>(xb) + tid;
             const int nx = nseg * H * 2;
-            q_u32x4 st[16], sts = {0u, 0u, 0u, 0u};
+            constexpr int CPY = TILE_XB / 16 / TILE_THREADS;  // copy steps of TILE_THREADS x 16 B that cover a full chunk
+            q_u32x4 st[CPY], sts = {0u, 0u, 0u, 0u};
+            const int nxs = nx * 256 / TILE_THREADS;      // steps this chunk needs (a set is 8 KiB: whole steps either way)
 #pragma unroll
-            for (int it = 0; it < 16; ++it)
-                if (it < nx) st[it] = src[it * 256];
+            for (int it = 0; it < CPY; ++it)
+                if (it < nxs) st[it] = src[it * TILE_THREADS];
             if (tid < nseg * H * 16) sts = reinterpret_cast<const q_u32x4*>(sq + (size_t)seg0 * (H * QSCL))[tid];
             __syncthreads();  // every wave is done reading the previous chunk
             if (c == 0) store_ep();
 #pragma unroll
-            for (int it = 0; it < 16; ++it)
-                if (it < nx) dst[it * 256] = st[it];
+            for (int it = 0; it < CPY; ++it)
+                if (it < nxs) dst[it * TILE_THREADS] = st[it];
             if (tid < nseg * H * 16) reinterpret_cast<q_u32x4*>(sb)[tid] = sts;
             __syncthreads();
         }
@@ -485,11 +499,11 @@ static inline int tile_qp(int op, int q_used) { return op == BCQ_OP_BWD_INPUT ? 
 static inline int tile_rt(int qp, int halves) { return qp == 1 ? (halves == 2 ? 2 : 4) : (qp == 2 ? 2 : 1); }
 
 // Work of one workgroup (a piece), in units of (row-tile group x segment).  The hardware starts the pieces in
-// index order as slots free up (two workgroups per compute unit of the 256), the longest first.  The size is chosen
+// index order as slots free up (one workgroup per compute unit of the 256), the longest first.  The size is chosen
 // per batch (choose_piece_units): small enough that the last round of pieces is not half empty, large enough that
 // the start-up of a piece (plan look-up, first memory round trip, one activation copy with two barriers per chunk)
 // stays a small part of its streaming time.  Layers with several chunks get pieces of three times the size.
-constexpr int kTileSlots = 512;
+constexpr int kTileSlots = 256 * (8 / TILE_WAVES);
 constexpr int kTileStartupUnits = 12;       // start-up of a piece, in units of streaming time (about 4 us)
 constexpr int kTileChunkStartupUnits = 7;   // every further chunk: a copy between two barriers
 constexpr int kTileMultiFactor = 3;
@@ -528,7 +542,7 @@ static BatchShape batch_shape(int op, int64_t T, int64_t N, int64_t K, int q, in
     const int mode = dx ? STREAM_DX : (op == BCQ_OP_FWD ? STREAM_FWD : STREAM_DALPHA);
     const int target = multi ? kTileMultiFactor * piece_units : piece_units;
     int per = (target + s.segs_main - 1) / s.segs_main;
-    per = (per + TILE_WAVES - 1) / TILE_WAVES * TILE_WAVES;  // whole rounds of the four waves
+    per = (per + TILE_WAVES - 1) / TILE_WAVES * TILE_WAVES;  // whole rounds of the waves
     if (per < TILE_WAVES) per = TILE_WAVES;
     // the epilogue operands of the piece and, with several chunks, its carried sums must fit their LDS area
     while (per > TILE_WAVES && tile_ep_bytes(mode, qp, s.rt_per_group, per, halves) +
@@ -543,14 +557,14 @@ static_assert(tile_ep_bytes(STREAM_DALPHA, 1, 4, TILE_WAVES, 1) + tile_part_byte
 static_assert(tile_ep_bytes(STREAM_DALPHA, 1, 2, TILE_WAVES, 2) + tile_part_bytes(2, TILE_WAVES, 2) <= TILE_AUX, "");
 static_assert(tile_ep_bytes(STREAM_FWD, 4, 1, TILE_WAVES, 2) + tile_part_bytes(1, TILE_WAVES, 2) <= TILE_AUX, "");
 
-// Picks the piece size for a batch: list scheduling (longest piece first, 512 slots) of the pieces every candidate size
+// Picks the piece size for a batch: list scheduling (longest piece first, one slot per compute unit) of the pieces every candidate size
 // gives, with the start-up costs above; the candidate with the shortest schedule wins.  Pure host arithmetic.
 static int choose_piece_units(int op, const bcq_batch_layer* layers, int64_t count, int64_t T, int q, int q_used) {
     int best = 96;
     double best_span = -1.0;
     std::vector<int64_t> costs;
     std::vector<int64_t> slots;
-    for (int cand = 48; cand <= 240; cand += 8) {
+    for (int cand = 48; cand <= 60 * TILE_WAVES; cand += 8) {
         costs.clear();
         for (int64_t l = 0; l < count; ++l) {
             const BatchShape s = batch_shape(op, T, layers[l].N, layers[l].K, q, q_used, cand);
@@ -558,7 +572,7 @@ static int choose_piece_units(int op, const bcq_batch_layer* layers, int64_t cou
             const int64_t fixed = kTileStartupUnits + (int64_t)(nch - 1) * kTileChunkStartupUnits;
             for (int32_t r0 = 0; r0 < s.nrtg; r0 += s.piece_rtg) {
                 const int32_t n = (s.nrtg - r0) < s.piece_rtg ? (s.nrtg - r0) : s.piece_rtg;
-                // the four waves take the groups in rounds: a piece lasts as long as its busiest wave
+                // the waves take the groups in rounds: a piece lasts as long as its busiest wave
                 const int64_t rounds = (n + TILE_WAVES - 1) / TILE_WAVES;
                 costs.push_back(rounds * TILE_WAVES * (int64_t)s.segs_main + fixed);
             }
