@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256) void quant_act_batched_kernel(const BatchLayer
 //   * Sign expansion with ONE operation per operand register: (word << s) | 0x77777777 turns bit b into the FP4 code
 //     0x7 | b << 3 = -6 (b = 1, i.e. +1) or +6 (b = 0, i.e. -1); the common factor -1/6 is applied in the epilogue.
 #ifndef TILE_WAVES_N
-#define TILE_WAVES_N 8  // 4 is supported too (then two workgroups per compute unit, chunks of half the size)
+#define TILE_WAVES_N 8  // 4 is supported too (then two workgroups per compute unit, chunks of half the size), and 12 with TILE_SETS_N 14
+                        // (170 registers per lane: 12 % slower at up to 8 tokens on the 2560-wide stack, 8 % faster on the input gradient at 16)
 #endif
 constexpr int TILE_WAVES = TILE_WAVES_N;
 constexpr int TILE_THREADS = 64 * TILE_WAVES;
@@ -156,7 +157,7 @@ __device__ __forceinline__ float row16_sum(float x) {
 }
 
 template <int MODE, int QP, int RT, bool TWO>
-__global__ __launch_bounds__(TILE_THREADS, 8 / TILE_WAVES) void stream_tile_batched_kernel(const BatchLayerDev* __restrict__ layers,
+__global__ __launch_bounds__(TILE_THREADS, (TILE_WAVES <= 4 ? 2 : 1)) void stream_tile_batched_kernel(const BatchLayerDev* __restrict__ layers,
                                                                       const BatchPiece* __restrict__ pieces,
                                                                       const unsigned char* __restrict__ ws, int T,
                                                                       float scale) {
@@ -316,18 +317,18 @@ __global__ __launch_bounds__(TILE_THREADS, 8 / TILE_WAVES) void stream_tile_batc
             const q_u32x4* src = reinterpret_cast<const q_u32x4*>(xq + (size_t)seg0 * (4 * H * QBLK)) + tid;
             q_u32x4* dst = reinterpret_cast<q_u32x4*>(xb) + tid;
             const int nx = nseg * H * 2;
-            constexpr int CPY = TILE_XB / 16 / TILE_THREADS;  // copy steps of TILE_THREADS x 16 B that cover a full chunk
+            constexpr int CPY = (TILE_XB / 16 + TILE_THREADS - 1) / TILE_THREADS;  // copy steps of all threads x 16 B for a full chunk
             q_u32x4 st[CPY], sts = {0u, 0u, 0u, 0u};
-            const int nxs = nx * 256 / TILE_THREADS;      // steps this chunk needs (a set is 8 KiB: whole steps either way)
+            const int nvec = nx * 256;  // 16-byte vectors of this chunk
 #pragma unroll
             for (int it = 0; it < CPY; ++it)
-                if (it < nxs) st[it] = src[it * TILE_THREADS];
+                if (tid + it * TILE_THREADS < nvec) st[it] = src[it * TILE_THREADS];
             if (tid < nseg * H * 16) sts = reinterpret_cast<const q_u32x4*>(sq + (size_t)seg0 * (H * QSCL))[tid];
             __syncthreads();  // every wave is done reading the previous chunk
             if (c == 0) store_ep();
 #pragma unroll
             for (int it = 0; it < CPY; ++it)
-                if (it < nxs) dst[it * TILE_THREADS] = st[it];
+                if (tid + it * TILE_THREADS < nvec) dst[it * TILE_THREADS] = st[it];
             if (tid < nseg * H * 16) reinterpret_cast<q_u32x4*>(sb)[tid] = sts;
             __syncthreads();
         }
@@ -503,7 +504,7 @@ static inline int tile_rt(int qp, int halves) { return qp == 1 ? (halves == 2 ? 
 // per batch (choose_piece_units): small enough that the last round of pieces is not half empty, large enough that
 // the start-up of a piece (plan look-up, first memory round trip, one activation copy with two barriers per chunk)
 // stays a small part of its streaming time.  Layers with several chunks get pieces of three times the size.
-constexpr int kTileSlots = 256 * (8 / TILE_WAVES);
+constexpr int kTileSlots = 256 * (TILE_WAVES <= 4 ? 2 : 1);
 constexpr int kTileStartupUnits = 12;       // start-up of a piece, in units of streaming time (about 4 us)
 constexpr int kTileChunkStartupUnits = 7;   // every further chunk: a copy between two barriers
 constexpr int kTileMultiFactor = 3;
